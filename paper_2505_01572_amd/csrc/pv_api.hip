@@ -1,0 +1,497 @@
+// Host side of the C ABI declared in include/pipeverify.h: argument checks, arena / workspace
+// layout, the per-step launch sequence, host mirrors of the cache state.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <new>
+#include "pv_kernels_common.h"
+
+static thread_local char g_err[512] = "";
+
+void pv_set_error(const char *fmt, ...)
+{
+    va_list ap; va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char *pv_last_error(void) { return g_err; }
+
+extern "C" const char *pv_strerror(int status)
+{
+    switch (status) {
+    case PV_OK: return "ok";
+    case PV_EINVAL: return "invalid argument";
+    case PV_ESTATE: return "call not valid in the current state";
+    case PV_ERANGE: return "value out of range";
+    case PV_EHIP: return "HIP runtime error";
+    case PV_ENOMEM: return "buffer too small";
+    default: return "unknown status";
+    }
+}
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+static const size_t STAGING_BYTES = 64u << 20;
+
+static int resolve_path(const pv_model_config *c)
+{
+    if (c->kernel_path == PV_PATH_AUTO) return c->dtype == PV_BF16 ? PV_PATH_MATRIX : PV_PATH_VECTOR;
+    return c->kernel_path;
+}
+
+static int check_config(const pv_model_config *c)
+{
+    if (!c) { pv_set_error("null config"); return PV_EINVAL; }
+    if (c->n_layers <= 0 || c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 ||
+        c->ffn_dim <= 0 || c->vocab <= 0) { pv_set_error("non-positive dimension"); return PV_EINVAL; }
+    if (c->n_q_heads % c->n_kv_heads) { pv_set_error("n_q_heads must be a multiple of n_kv_heads"); return PV_EINVAL; }
+    if (c->head_dim % 2 || c->head_dim > 256) { pv_set_error("head_dim must be even and <= 256"); return PV_EINVAL; }
+    if (c->dtype != PV_F32 && c->dtype != PV_BF16) { pv_set_error("bad dtype"); return PV_EINVAL; }
+    if (!is_pow2(c->page_tokens)) { pv_set_error("page_tokens must be a power of two"); return PV_EINVAL; }
+    if (c->max_gamma < 1 || c->max_gamma > PV_MAX_ROWS) { pv_set_error("max_gamma must be in [1, %d]", PV_MAX_ROWS); return PV_EINVAL; }
+    if (!(c->rms_eps > 0) || !(c->rope_base > 1)) { pv_set_error("bad rms_eps / rope_base"); return PV_EINVAL; }
+    const int path = resolve_path(c);
+    if (path != PV_PATH_VECTOR && path != PV_PATH_MATRIX) { pv_set_error("bad kernel_path"); return PV_EINVAL; }
+    const int qd = c->n_q_heads * c->head_dim;
+    if (c->d_model % 4 || c->ffn_dim % 4 || qd % 4) { pv_set_error("d_model, ffn_dim, q_dim must be multiples of 4"); return PV_EINVAL; }
+    if (path == PV_PATH_MATRIX) {
+        if (c->dtype != PV_BF16) { pv_set_error("matrix path needs bf16 storage"); return PV_EINVAL; }
+        if (c->d_model % 32 || c->ffn_dim % 32 || qd % 32 || c->vocab % 16 || c->head_dim % 16 || c->page_tokens < 16) {
+            pv_set_error("matrix path: d_model, ffn_dim, q_dim %% 32, vocab, head_dim %% 16, page_tokens >= 16 required");
+            return PV_EINVAL;
+        }
+    }
+    return PV_OK;
+}
+
+static void tensor_dims(const pv_model_config *c, int kind, int64_t *rows, int64_t *cols)
+{
+    const int64_t d = c->d_model, qd = (int64_t)c->n_q_heads * c->head_dim, kvd = (int64_t)c->n_kv_heads * c->head_dim;
+    switch (kind) {
+    case PV_T_EMBED: case PV_T_LM_HEAD: *rows = c->vocab; *cols = d; break;
+    case PV_T_ATTN_NORM: case PV_T_FFN_NORM: case PV_T_FINAL_NORM: *rows = 1; *cols = d; break;
+    case PV_T_WQ: *rows = qd; *cols = d; break;
+    case PV_T_WK: case PV_T_WV: *rows = kvd; *cols = d; break;
+    case PV_T_WO: *rows = d; *cols = qd; break;
+    case PV_T_WG: case PV_T_WU: *rows = c->ffn_dim; *cols = d; break;
+    case PV_T_WD: *rows = d; *cols = c->ffn_dim; break;
+    default: *rows = *cols = 0;
+    }
+}
+
+// Lays the arena out; fills refs when m != nullptr.  Returns total bytes.
+static size_t layout_arena(const pv_model_config *c, pv_model *m)
+{
+    const int path = resolve_path(c);
+    const size_t elt = c->dtype == PV_BF16 ? 2 : 4;
+    size_t off = 0;
+    auto place = [&](int kind, int layer) {
+        int64_t r, k; tensor_dims(c, kind, &r, &k);
+        pv_tensor_ref t; t.off = off; t.rows = r; t.cols = k; t.loaded_rows = 0; t.strip_mul = 1; t.strip_add = 0;
+        off = align_up(off + (size_t)r * k * elt, 256);
+        if (m) { if (layer < 0) m->global[kind] = t; else m->layer[(size_t)layer * PV_T_NKINDS + kind] = t; }
+    };
+    place(PV_T_EMBED, -1);
+    for (int l = 0; l < c->n_layers; ++l) {
+        place(PV_T_ATTN_NORM, l);
+        place(PV_T_WQ, l); place(PV_T_WK, l); place(PV_T_WV, l);     // contiguous: one fused QKV region
+        place(PV_T_WO, l);
+        place(PV_T_FFN_NORM, l);
+        const size_t gu = off;
+        place(PV_T_WG, l); place(PV_T_WU, l);
+        if (m && path == PV_PATH_MATRIX) {                            // gate/up strips interleaved in one region
+            pv_tensor_ref &g = m->layer[(size_t)l * PV_T_NKINDS + PV_T_WG], &u = m->layer[(size_t)l * PV_T_NKINDS + PV_T_WU];
+            g.off = u.off = gu; g.strip_mul = u.strip_mul = 2; g.strip_add = 0; u.strip_add = 1;
+        }
+        place(PV_T_WD, l);
+    }
+    place(PV_T_FINAL_NORM, -1);
+    place(PV_T_LM_HEAD, -1);
+    if (m) m->inv_freq_off = off;
+    off = align_up(off + (size_t)(c->head_dim / 2) * sizeof(double), 256);
+    return off;
+}
+
+extern "C" int pv_model_bytes(const pv_model_config *cfg, size_t *weight_bytes, size_t *staging_bytes)
+{
+    int rc = check_config(cfg);
+    if (rc != PV_OK) return rc;
+    if (!weight_bytes || !staging_bytes) { pv_set_error("null output pointer"); return PV_EINVAL; }
+    *weight_bytes = layout_arena(cfg, nullptr);
+    *staging_bytes = resolve_path(cfg) == PV_PATH_MATRIX ? STAGING_BYTES : 256;
+    return PV_OK;
+}
+
+extern "C" int pv_model_create(const pv_model_config *cfg, void *d_weights, size_t weight_bytes,
+                               void *d_staging, size_t staging_bytes, pv_model **out)
+{
+    int rc = check_config(cfg);
+    if (rc != PV_OK) return rc;
+    if (!d_weights || !d_staging || !out) { pv_set_error("null pointer"); return PV_EINVAL; }
+    if (((uintptr_t)d_weights | (uintptr_t)d_staging) & 255) { pv_set_error("device buffers must be 256-byte aligned"); return PV_EINVAL; }
+    size_t need_w, need_s;
+    pv_model_bytes(cfg, &need_w, &need_s);
+    if (weight_bytes < need_w || staging_bytes < need_s) { pv_set_error("arena %zu < %zu or staging %zu < %zu", weight_bytes, need_w, staging_bytes, need_s); return PV_ENOMEM; }
+    pv_model *m = new (std::nothrow) pv_model();
+    if (!m) return PV_ENOMEM;
+    m->cfg = *cfg; m->path = resolve_path(cfg); m->elt = cfg->dtype == PV_BF16 ? 2 : 4;
+    m->d_weights = (char *)d_weights; m->weight_bytes = weight_bytes;
+    m->d_staging = (char *)d_staging; m->staging_bytes = staging_bytes;
+    m->layer = (pv_tensor_ref *)calloc((size_t)cfg->n_layers * PV_T_NKINDS, sizeof(pv_tensor_ref));
+    if (!m->layer) { delete m; return PV_ENOMEM; }
+    layout_arena(cfg, m);
+    m->inv_freq_uploaded = false;
+    int dev = 0; hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        pv_set_error("no HIP device"); free(m->layer); delete m; return PV_EHIP;
+    }
+    m->n_cus = prop.multiProcessorCount;
+    // rotary inverse frequencies base^(-2i/head_dim), double
+    const int half = cfg->head_dim / 2;
+    double *inv = (double *)malloc(sizeof(double) * half);
+    for (int i = 0; i < half; ++i) inv[i] = pow(cfg->rope_base, -2.0 * (double)i / (double)cfg->head_dim);
+    hipError_t e = hipMemcpy(m->d_weights + m->inv_freq_off, inv, sizeof(double) * half, hipMemcpyHostToDevice);
+    free(inv);
+    if (e != hipSuccess) { pv_set_error("upload of rotary table failed: %s", hipGetErrorString(e)); free(m->layer); delete m; return PV_EHIP; }
+    *out = m;
+    return PV_OK;
+}
+
+extern "C" void pv_model_destroy(pv_model *m)
+{
+    if (!m) return;
+    free(m->layer);
+    delete m;
+}
+
+extern "C" int pv_load_weights(pv_model *m, int32_t kind, int32_t layer, int64_t row_begin, int64_t row_count,
+                               const void *host_rows, void *hip_stream)
+{
+    if (!m || !host_rows) { pv_set_error("null pointer"); return PV_EINVAL; }
+    if (kind < 0 || kind >= PV_T_NKINDS) { pv_set_error("bad tensor kind %d", kind); return PV_EINVAL; }
+    const bool global = kind == PV_T_EMBED || kind == PV_T_FINAL_NORM || kind == PV_T_LM_HEAD;
+    if (!global && (layer < 0 || layer >= m->cfg.n_layers)) { pv_set_error("bad layer %d", layer); return PV_EINVAL; }
+    pv_tensor_ref &t = global ? m->global[kind] : m->layer[(size_t)layer * PV_T_NKINDS + kind];
+    if (row_begin < 0 || row_count <= 0 || row_begin + row_count > t.rows) { pv_set_error("rows [%lld, +%lld) outside tensor of %lld rows", (long long)row_begin, (long long)row_count, (long long)t.rows); return PV_ERANGE; }
+    hipStream_t s = (hipStream_t)hip_stream;
+    const size_t nbytes = (size_t)row_count * t.cols * m->elt;
+    const bool tiled = m->path == PV_PATH_MATRIX && t.rows > 1 && kind != PV_T_EMBED;
+    if (!tiled) {
+        PV_HIP(hipMemcpyAsync(m->d_weights + t.off + (size_t)row_begin * t.cols * m->elt, host_rows, nbytes, hipMemcpyHostToDevice, s));
+        PV_HIP(hipStreamSynchronize(s));
+    } else {
+        if ((row_begin | row_count) & 15) { pv_set_error("matrix path: row_begin and row_count must be multiples of 16"); return PV_EINVAL; }
+        if (nbytes > m->staging_bytes) { pv_set_error("chunk of %zu bytes exceeds staging buffer of %zu", nbytes, m->staging_bytes); return PV_ENOMEM; }
+        PV_HIP(hipMemcpyAsync(m->d_staging, host_rows, nbytes, hipMemcpyHostToDevice, s));
+        int rc = pv_mat_repack(m, t, row_begin, row_count, s);
+        if (rc != PV_OK) return rc;
+        PV_HIP(hipStreamSynchronize(s));
+    }
+    t.loaded_rows += row_count;
+    return PV_OK;
+}
+
+static int model_complete(const pv_model *m)
+{
+    for (int k = 0; k < PV_T_NKINDS; ++k) {
+        const bool global = k == PV_T_EMBED || k == PV_T_FINAL_NORM || k == PV_T_LM_HEAD;
+        if (global) { if (m->global[k].loaded_rows < m->global[k].rows) return 0; }
+        else for (int l = 0; l < m->cfg.n_layers; ++l) {
+            const pv_tensor_ref &t = m->layer[(size_t)l * PV_T_NKINDS + k];
+            if (t.loaded_rows < t.rows) return 0;
+        }
+    }
+    return 1;
+}
+
+// ---- workspace layout ----
+static size_t layout_ws(const pv_model *m, int rows_cap, int n_pages, pv_ws *w, char *base)
+{
+    const pv_model_config &c = m->cfg;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return base ? base + o : (char *)nullptr; };
+    const size_t qd = (size_t)c.n_q_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim, R = rows_cap;
+    char *p;
+    p = take(sizeof(pv_dev_state)); if (w) w->state = (pv_dev_state *)p;
+    p = take(sizeof(int32_t) * n_pages); if (w) w->page_table = (int32_t *)p;
+    p = take(sizeof(float2) * R * (c.head_dim / 2)); if (w) w->rope = (float2 *)p;
+    p = take(4 * R * c.d_model); if (w) w->x = (float *)p;
+    p = take(4 * R * c.d_model); if (w) w->h = (float *)p;
+    p = take(4 * R * qd); if (w) w->q = (float *)p;
+    p = take(4 * R * kvd); if (w) w->k = (float *)p;
+    p = take(4 * R * kvd); if (w) w->v = (float *)p;
+    p = take(4 * R * qd); if (w) w->attn = (float *)p;
+    p = take(4 * R * c.ffn_dim); if (w) w->gate = (float *)p;
+    p = take(4 * R * c.ffn_dim); if (w) w->up = (float *)p;
+    p = take(4 * R * (size_t)c.vocab); if (w) w->logits = (float *)p;
+    const size_t pf = m->path == PV_PATH_MATRIX ? pv_mat_part_floats(m, rows_cap) : 0;
+    p = take(4 * pf + 256); if (w) { w->part = (float *)p; w->part_floats = pf; }
+    return off;
+}
+
+static inline int rows_cap_of(const pv_model *m) { return (m->cfg.max_gamma + PV_ROW_PAD - 1) / PV_ROW_PAD * PV_ROW_PAD; }
+
+extern "C" int pv_cache_bytes(const pv_model *m, int32_t max_tokens, size_t *page_pool_bytes, size_t *workspace_bytes)
+{
+    if (!m || !page_pool_bytes || !workspace_bytes) { pv_set_error("null pointer"); return PV_EINVAL; }
+    if (max_tokens <= 0) { pv_set_error("max_tokens must be positive"); return PV_ERANGE; }
+    const pv_model_config &c = m->cfg;
+    const int n_pages = (max_tokens + c.page_tokens - 1) / c.page_tokens;
+    *page_pool_bytes = align_up((size_t)c.n_layers * n_pages * c.n_kv_heads * 2 * c.page_tokens * c.head_dim * m->elt, 256);
+    *workspace_bytes = layout_ws(m, rows_cap_of(m), n_pages, nullptr, nullptr);
+    return PV_OK;
+}
+
+extern "C" int pv_cache_create(const pv_model *m, void *d_page_pool, size_t page_pool_bytes, void *d_workspace,
+                               size_t workspace_bytes, int32_t max_tokens, pv_cache **out)
+{
+    if (!m || !d_page_pool || !d_workspace || !out) { pv_set_error("null pointer"); return PV_EINVAL; }
+    if (((uintptr_t)d_page_pool | (uintptr_t)d_workspace) & 255) { pv_set_error("device buffers must be 256-byte aligned"); return PV_EINVAL; }
+    size_t need_p, need_w;
+    int rc = pv_cache_bytes(m, max_tokens, &need_p, &need_w);
+    if (rc != PV_OK) return rc;
+    if (page_pool_bytes < need_p || workspace_bytes < need_w) { pv_set_error("pool %zu < %zu or workspace %zu < %zu", page_pool_bytes, need_p, workspace_bytes, need_w); return PV_ENOMEM; }
+    pv_cache *c = new (std::nothrow) pv_cache();
+    if (!c) return PV_ENOMEM;
+    c->m = m; c->d_pool = (char *)d_page_pool; c->pool_bytes = page_pool_bytes;
+    c->d_ws = (char *)d_workspace; c->ws_bytes = workspace_bytes;
+    c->max_tokens = max_tokens; c->n_pages = (max_tokens + m->cfg.page_tokens - 1) / m->cfg.page_tokens;
+    c->rows_cap = rows_cap_of(m);
+    layout_ws(m, c->rows_cap, c->n_pages, &c->ws, c->d_ws);
+    c->len = 0; c->pending = -1; c->last_rows = 0; c->in_flight = false; c->flight_stream = nullptr; c->io = nullptr;
+    if (hipHostMalloc((void **)&c->io, sizeof(pv_host_io), hipHostMallocDefault) != hipSuccess) {
+        pv_set_error("hipHostMalloc failed"); delete c; return PV_EHIP;
+    }
+    memset(c->io, 0, sizeof(pv_host_io));
+    // device state, identity page table; activations zeroed once so padding rows are finite
+    hipError_t e = hipMemset(c->d_ws, 0, need_w);
+    int32_t *ident = (int32_t *)malloc(sizeof(int32_t) * c->n_pages);
+    for (int i = 0; i < c->n_pages; ++i) ident[i] = i;
+    if (e == hipSuccess) e = hipMemcpy(c->ws.page_table, ident, sizeof(int32_t) * c->n_pages, hipMemcpyHostToDevice);
+    free(ident);
+    pv_dev_state st; memset(&st, 0, sizeof(st)); st.pending = -1;
+    if (e == hipSuccess) e = hipMemcpy(c->ws.state, &st, sizeof(st), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { pv_set_error("cache initialisation failed: %s", hipGetErrorString(e)); (void)hipHostFree(c->io); delete c; return PV_EHIP; }
+    *out = c;
+    return PV_OK;
+}
+
+extern "C" void pv_cache_destroy(pv_cache *c)
+{
+    if (!c) return;
+    if (c->io) (void)hipHostFree(c->io);
+    delete c;
+}
+
+extern "C" int pv_cache_set_page_table(pv_cache *c, const int32_t *phys_pages, int32_t n_pages, void *hip_stream)
+{
+    if (!c || !phys_pages) { pv_set_error("null pointer"); return PV_EINVAL; }
+    if (c->len != 0 || c->in_flight) { pv_set_error("page table can only be replaced on an empty, idle cache"); return PV_ESTATE; }
+    if (n_pages != c->n_pages) { pv_set_error("n_pages %d != %d", n_pages, c->n_pages); return PV_EINVAL; }
+    char *seen = (char *)calloc(n_pages, 1);
+    for (int i = 0; i < n_pages; ++i) {
+        if (phys_pages[i] < 0 || phys_pages[i] >= n_pages || seen[phys_pages[i]]) { free(seen); pv_set_error("page table is not a permutation"); return PV_EINVAL; }
+        seen[phys_pages[i]] = 1;
+    }
+    free(seen);
+    hipStream_t s = (hipStream_t)hip_stream;
+    PV_HIP(hipMemcpyAsync(c->ws.page_table, phys_pages, sizeof(int32_t) * n_pages, hipMemcpyHostToDevice, s));
+    PV_HIP(hipStreamSynchronize(s));
+    return PV_OK;
+}
+
+// ---- the step ----
+
+static int enqueue_block(pv_cache *c, const int32_t *tokens, int rows, int mode, hipStream_t s)
+{
+    const pv_model *m = c->m;
+    for (int j = 0; j < rows; ++j)
+        if (tokens[j] < 0 || tokens[j] >= m->cfg.vocab) { pv_set_error("token id %d at position %d outside [0, %d)", tokens[j], j, m->cfg.vocab); return PV_ERANGE; }
+    memcpy(c->io->draft, tokens, sizeof(int32_t) * rows);
+    c->io->hdr[2] = rows; c->io->hdr[3] = mode;
+    c->last_rows = rows;
+    PV_HIP(hipMemcpyAsync(c->ws.state->draft, c->io->draft, sizeof(int32_t) * rows, hipMemcpyHostToDevice, s));
+    int rc = pv_k_set_step(c, rows, mode, s);
+    if (rc != PV_OK) return rc;
+    rc = m->path == PV_PATH_MATRIX ? pv_mat_run_block(c, s) : pv_vec_run_block(c, s);
+    if (rc != PV_OK) return rc;
+    // accepted, next_token -> mailbox; len/pending follow from them on the host
+    PV_HIP(hipMemcpyAsync(c->io->result, &c->ws.state->accepted, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    return PV_OK;
+}
+
+static void absorb_result(pv_cache *c)
+{
+    c->len += c->io->result[0];
+    c->pending = c->io->result[1];
+}
+
+static int check_ready(const pv_cache *c)
+{
+    if (!c) { pv_set_error("null cache"); return PV_EINVAL; }
+    if (c->in_flight) { pv_set_error("a verify is in flight on this cache; call pv_verify_wait first"); return PV_ESTATE; }
+    if (!model_complete(c->m)) { pv_set_error("not all weights have been loaded"); return PV_ESTATE; }
+    return PV_OK;
+}
+
+extern "C" int pv_prefill(pv_cache *c, const int32_t *tokens, int32_t n, void *hip_stream)
+{
+    int rc = check_ready(c);
+    if (rc != PV_OK) return rc;
+    if (!tokens) { pv_set_error("null tokens"); return PV_EINVAL; }
+    if (n <= 0 || c->len + n > c->max_tokens) { pv_set_error("prefill of %d tokens does not fit (length %d, max %d)", n, c->len, c->max_tokens); return PV_ERANGE; }
+    for (int j = 0; j < n; ++j)
+        if (tokens[j] < 0 || tokens[j] >= c->m->cfg.vocab) { pv_set_error("token id %d at position %d outside [0, %d)", tokens[j], j, c->m->cfg.vocab); return PV_ERANGE; }
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int chunk = c->m->cfg.max_gamma;
+    for (int off = 0; off < n; off += chunk) {
+        const int rows = n - off < chunk ? n - off : chunk;
+        const bool last = off + rows >= n;
+        rc = enqueue_block(c, tokens + off, rows, last ? PV_MODE_PREFILL_LAST : PV_MODE_PREFILL_MID, s);
+        if (rc != PV_OK) return rc;
+        PV_HIP(hipStreamSynchronize(s));          // the mailbox is reused by the next chunk
+        absorb_result(c);
+    }
+    return PV_OK;
+}
+
+static int verify_checks(pv_cache *c, int32_t prefix_len, const int32_t *draft, int32_t gamma)
+{
+    int rc = check_ready(c);
+    if (rc != PV_OK) return rc;
+    if (!draft) { pv_set_error("null draft"); return PV_EINVAL; }
+    if (prefix_len != c->len) { pv_set_error("prefix_len %d != cache length %d", prefix_len, c->len); return PV_ESTATE; }
+    if (gamma < 1 || gamma > c->m->cfg.max_gamma) { pv_set_error("gamma %d outside [1, %d]", gamma, c->m->cfg.max_gamma); return PV_ERANGE; }
+    if (c->len + gamma > c->max_tokens) { pv_set_error("length %d + gamma %d exceeds max_tokens %d", c->len, gamma, c->max_tokens); return PV_ERANGE; }
+    return PV_OK;
+}
+
+extern "C" int pv_verify_async(pv_cache *c, int32_t prefix_len, const int32_t *draft, int32_t gamma, void *hip_stream)
+{
+    int rc = verify_checks(c, prefix_len, draft, gamma);
+    if (rc != PV_OK) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    rc = enqueue_block(c, draft, gamma, PV_MODE_VERIFY, s);
+    if (rc != PV_OK) return rc;
+    c->in_flight = true; c->flight_stream = s;
+    return PV_OK;
+}
+
+extern "C" int pv_verify_wait(pv_cache *c, int32_t *accepted_len, int32_t *next_token)
+{
+    if (!c || !accepted_len || !next_token) { pv_set_error("null pointer"); return PV_EINVAL; }
+    if (!c->in_flight) { pv_set_error("no verify in flight"); return PV_ESTATE; }
+    c->in_flight = false;
+    PV_HIP(hipStreamSynchronize(c->flight_stream));
+    absorb_result(c);
+    *accepted_len = c->io->result[0];
+    *next_token = c->io->result[1];
+    return PV_OK;
+}
+
+extern "C" int pv_verify(pv_cache *c, int32_t prefix_len, const int32_t *draft, int32_t gamma,
+                         int32_t *accepted_len, int32_t *next_token, void *hip_stream)
+{
+    if (!accepted_len || !next_token) { pv_set_error("null output pointer"); return PV_EINVAL; }
+    int rc = pv_verify_async(c, prefix_len, draft, gamma, hip_stream);
+    if (rc != PV_OK) return rc;
+    return pv_verify_wait(c, accepted_len, next_token);
+}
+
+extern "C" int pv_rollback(pv_cache *c, int32_t new_len, void *hip_stream)
+{
+    if (!c) { pv_set_error("null cache"); return PV_EINVAL; }
+    if (c->in_flight) { pv_set_error("a verify is in flight on this cache"); return PV_ESTATE; }
+    if (new_len < 0 || new_len > c->len) { pv_set_error("new_len %d outside [0, %d]", new_len, c->len); return PV_ERANGE; }
+    hipStream_t s = (hipStream_t)hip_stream;
+    int rc = pv_k_set_state(c, new_len, -1, s);
+    if (rc != PV_OK) return rc;
+    PV_HIP(hipStreamSynchronize(s));
+    c->len = new_len; c->pending = -1;
+    return PV_OK;
+}
+
+extern "C" int pv_cache_len(const pv_cache *c, int32_t *len, int32_t *pending)
+{
+    if (!c) { pv_set_error("null cache"); return PV_EINVAL; }
+    if (len) *len = c->len;
+    if (pending) *pending = c->pending;
+    return PV_OK;
+}
+
+extern "C" int pv_cache_set_pending(pv_cache *c, int32_t token, void *hip_stream)
+{
+    if (!c) { pv_set_error("null cache"); return PV_EINVAL; }
+    if (c->in_flight) { pv_set_error("a verify is in flight on this cache"); return PV_ESTATE; }
+    if (token < -1 || token >= c->m->cfg.vocab) { pv_set_error("token %d out of range", token); return PV_ERANGE; }
+    hipStream_t s = (hipStream_t)hip_stream;
+    int rc = pv_k_set_state(c, c->len, token, s);
+    if (rc != PV_OK) return rc;
+    PV_HIP(hipStreamSynchronize(s));
+    c->pending = token;
+    return PV_OK;
+}
+
+extern "C" int pv_debug_logits(pv_cache *c, float *host_out, int32_t *rows, void *hip_stream)
+{
+    if (!c) { pv_set_error("null cache"); return PV_EINVAL; }
+    if (c->in_flight) { pv_set_error("a verify is in flight on this cache"); return PV_ESTATE; }
+    if (rows) *rows = c->last_rows;
+    if (!host_out || c->last_rows == 0) return PV_OK;
+    hipStream_t s = (hipStream_t)hip_stream;
+    PV_HIP(hipMemcpyAsync(host_out, c->ws.logits, sizeof(float) * (size_t)c->last_rows * c->m->cfg.vocab, hipMemcpyDeviceToHost, s));
+    PV_HIP(hipStreamSynchronize(s));
+    return PV_OK;
+}
+
+extern "C" int pv_debug_pred(pv_cache *c, int32_t *host_out, int32_t *rows, void *hip_stream)
+{
+    if (!c) { pv_set_error("null cache"); return PV_EINVAL; }
+    if (c->in_flight) { pv_set_error("a verify is in flight on this cache"); return PV_ESTATE; }
+    if (rows) *rows = c->last_rows;
+    if (!host_out || c->last_rows == 0) return PV_OK;
+    hipStream_t s = (hipStream_t)hip_stream;
+    PV_HIP(hipMemcpyAsync(host_out, c->ws.state->pred, sizeof(int32_t) * c->last_rows, hipMemcpyDeviceToHost, s));
+    PV_HIP(hipStreamSynchronize(s));
+    return PV_OK;
+}
+
+extern "C" int pv_cache_export(pv_cache *c, void *host_out, size_t nbytes, void *hip_stream)
+{
+    if (!c || !host_out) { pv_set_error("null pointer"); return PV_EINVAL; }
+    if (c->in_flight) { pv_set_error("a verify is in flight on this cache"); return PV_ESTATE; }
+    const pv_model_config &f = c->m->cfg;
+    const size_t total = (size_t)f.n_layers * 2 * c->len * f.n_kv_heads * f.head_dim;
+    if (nbytes < total * c->m->elt) { pv_set_error("export needs %zu bytes, got %zu", total * c->m->elt, nbytes); return PV_ENOMEM; }
+    // bounce through the logits buffer (dead between steps) in chunks
+    hipStream_t s = (hipStream_t)hip_stream;
+    const size_t cap = (size_t)c->rows_cap * f.vocab * sizeof(float) / c->m->elt;
+    for (size_t e0 = 0; e0 < total; e0 += cap) {
+        const size_t n = total - e0 < cap ? total - e0 : cap;
+        int rc = pv_k_export(c, e0, n, c->ws.logits, s);
+        if (rc != PV_OK) return rc;
+        PV_HIP(hipMemcpyAsync((char *)host_out + e0 * c->m->elt, c->ws.logits, n * c->m->elt, hipMemcpyDeviceToHost, s));
+        PV_HIP(hipStreamSynchronize(s));
+    }
+    c->last_rows = 0;           // the logits buffer no longer holds a block's logits
+    return PV_OK;
+}
+
+extern "C" int pv_step_bytes(const pv_cache *c, int32_t gamma, uint64_t *bytes)
+{
+    if (!c || !bytes) { pv_set_error("null pointer"); return PV_EINVAL; }
+    const pv_model *m = c->m;
+    const pv_model_config &f = m->cfg;
+    uint64_t w = 0;
+    for (int k = 0; k < PV_T_NKINDS; ++k) {
+        if (k == PV_T_EMBED) continue;
+        int64_t r, cc; tensor_dims(&f, k, &r, &cc);
+        const bool global = k == PV_T_FINAL_NORM || k == PV_T_LM_HEAD;
+        w += (uint64_t)r * cc * m->elt * (global ? 1 : f.n_layers);
+    }
+    const uint64_t kv_tok = (uint64_t)f.n_layers * 2 * f.n_kv_heads * f.head_dim * m->elt;
+    *bytes = w + kv_tok * (uint64_t)(c->len + gamma) + kv_tok * (uint64_t)gamma;
+    return PV_OK;
+}

@@ -1,0 +1,110 @@
+// Internal declarations shared by the host API and the two kernel families.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "pipeverify.h"
+
+#define PV_MAX_ROWS 64          // hard cap on rows per block (max_gamma)
+#define PV_ROW_PAD 16           // activation buffers are padded to a multiple of this many rows
+
+// step modes written into pv_dev_state::mode
+enum { PV_MODE_VERIFY = 0, PV_MODE_PREFILL_LAST = 1, PV_MODE_PREFILL_MID = 2 };
+
+// Per-cache state that lives in device memory so that a step needs no host-side patching:
+// every kernel reads the cache length and row count from here.
+struct pv_dev_state {
+    int32_t len;                // committed tokens
+    int32_t pending;            // stage's own prediction for position len, -1 = unknown
+    int32_t gamma;              // rows of the running block
+    int32_t mode;
+    int32_t accepted, next_token;
+    int32_t error;              // set by kernels on an impossible condition
+    int32_t pad;
+    int32_t draft[PV_MAX_ROWS];
+    int32_t pred[PV_MAX_ROWS];
+};
+
+// pinned host mailbox (one per cache)
+struct pv_host_io {
+    int32_t draft[PV_MAX_ROWS];
+    int32_t hdr[4];             // len, pending, gamma, mode
+    int32_t result[4];          // accepted, next_token, len, pending
+};
+
+struct pv_tensor_ref {
+    size_t  off;                // byte offset in the weight arena
+    int64_t rows, cols;
+    int64_t loaded_rows;
+    // matrix path: 16-row strip i of this tensor is strip (i*strip_mul + strip_add) of the tiled
+    // region starting at `off` (gate/up are interleaved strip by strip; q,k,v are concatenated)
+    int32_t strip_mul, strip_add;
+};
+
+struct pv_model {
+    pv_model_config cfg;
+    int path;                   // PV_PATH_VECTOR or PV_PATH_MATRIX (resolved)
+    int elt;                    // bytes per stored element
+    char *d_weights; size_t weight_bytes;
+    char *d_staging; size_t staging_bytes;
+    pv_tensor_ref *layer;       // [n_layers][PV_T_NKINDS]
+    pv_tensor_ref global[PV_T_NKINDS];
+    size_t inv_freq_off;        // double[head_dim/2]
+    bool inv_freq_uploaded;
+    int n_cus;
+};
+
+struct pv_ws {                  // pointers into the caller's workspace
+    pv_dev_state *state;
+    int32_t *page_table;
+    float2 *rope;               // [rows][head_dim/2] (cos, sin)
+    float *x, *h, *q, *k, *v, *attn, *gate, *up, *logits;
+    float *part;                // matrix path: split-K partial sums
+    size_t part_floats;
+};
+
+struct pv_cache {
+    const pv_model *m;
+    char *d_pool; size_t pool_bytes;
+    char *d_ws; size_t ws_bytes;
+    int32_t max_tokens, n_pages, rows_cap;
+    pv_ws ws;
+    pv_host_io *io;             // pinned
+    int32_t len, pending, last_rows;
+    bool in_flight; hipStream_t flight_stream;
+};
+
+static inline const pv_tensor_ref &pv_tref(const pv_model *m, int kind, int layer)
+{
+    if (kind == PV_T_EMBED || kind == PV_T_FINAL_NORM || kind == PV_T_LM_HEAD) return m->global[kind];
+    return m->layer[(size_t)layer * PV_T_NKINDS + kind];
+}
+
+// KV page pool addressing, in elements:
+//   block(layer, phys_page, kv_head, which) = (((layer*n_pages + phys)*n_kv_heads + kv_head)*2 + which) * page_tokens*head_dim
+//   K block: [token][head_dim]      V block: [head_dim][token]   (V is kept transposed inside a page)
+struct pv_kv_geom {
+    int32_t n_pages, n_kv_heads, page_tokens, head_dim, page_shift;
+};
+
+__host__ __device__ static inline size_t pv_kv_block(const pv_kv_geom &g, int layer, int phys, int kvh, int which)
+{
+    return ((((size_t)layer * g.n_pages + phys) * g.n_kv_heads + kvh) * 2 + which) * (size_t)(g.page_tokens * g.head_dim);
+}
+
+// ---- kernel-family entry points (host functions that enqueue on `s`) ----
+int pv_vec_run_block(pv_cache *c, hipStream_t s);        // pv_kernels_vector.hip
+int pv_mat_run_block(pv_cache *c, hipStream_t s);        // pv_kernels_matrix.hip
+int pv_mat_repack(const pv_model *m, const pv_tensor_ref &t, int64_t row_begin, int64_t row_count, hipStream_t s);
+size_t pv_mat_part_floats(const pv_model *m, int rows_cap);
+int pv_common_export(pv_cache *c, void *d_out, hipStream_t s);   // gathers logical K/V into d_out
+void pv_set_error(const char *fmt, ...);
+
+#define PV_HIP(call)                                                                        \
+    do {                                                                                    \
+        hipError_t e_ = (call);                                                             \
+        if (e_ != hipSuccess) {                                                             \
+            pv_set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return PV_EHIP;                                                                 \
+        }                                                                                   \
+    } while (0)

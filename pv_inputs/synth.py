@@ -151,3 +151,12 @@ def perturb_drafts(tokens, alpha: float, vocab: int, seed: int, step: int):
     u = unit_draws(seed, n, stream=2 * step + 1)
     r = uniform_tokens(seed, n, vocab, stream=2 * step + 2)
     return np.where(u < (1.0 - alpha), r, tokens).astype(np.int32)
+
+
+def iter_row_chunks(m: ModelShape, kind: str, layer: int, max_rows: int, gains: str = "ones"):
+    """Yield (row_begin, rows[row_count, in_features]) pieces of one tensor, at most max_rows rows each."""
+    shape = tensor_shape(m, kind)
+    rows, cols = (1, shape[0]) if len(shape) == 1 else shape
+    for r0 in range(0, rows, max_rows):
+        n = min(max_rows, rows - r0)
+        yield r0, fill_tensor(m, kind, layer, start=r0 * cols, count=n * cols, gains=gains).reshape(n, cols)

@@ -1,0 +1,31 @@
+"""GPU-side test plumbing: build a library model from the seeded generator."""
+import numpy as np
+
+import pv_inputs
+import paper_2505_01572_amd as pv
+
+
+def gpu_model(shape, gains="ones", max_gamma=16, kernel_path=pv.PATH_AUTO, overrides=None):
+    m = pv.Model(shape, max_gamma=max_gamma, kernel_path=kernel_path)
+    for kind, layer in pv_inputs.iter_tensors(shape):
+        tshape = pv_inputs.tensor_shape(shape, kind)
+        cols = tshape[-1]
+        if overrides and (kind, layer) in overrides:
+            arr = np.ascontiguousarray(overrides[(kind, layer)]).reshape(-1, cols)
+            step = m.chunk_rows(cols)
+            for r0 in range(0, arr.shape[0], step):
+                m.load_weights(kind, layer, r0, arr[r0:r0 + step])
+            continue
+        for r0, rows in pv_inputs.iter_row_chunks(shape, kind, layer, m.chunk_rows(cols), gains=gains):
+            m.load_weights(kind, layer, r0, rows)
+    return m
+
+
+def logit_scale(ref_logits):
+    """Per-row RMS of the oracle's logits: the scale bf16 tolerances are relative to."""
+    return np.sqrt((np.asarray(ref_logits, dtype=np.float64) ** 2).mean(axis=-1, keepdims=True))
+
+
+def top2_margin(ref_logits):
+    s = np.sort(np.asarray(ref_logits), axis=-1)
+    return s[..., -1] - s[..., -2]
