@@ -95,7 +95,7 @@ __host__ __device__ static inline size_t pv_kv_block(const pv_kv_geom &g, int la
 // ---- kernel-family entry points (host functions that enqueue on `s`) ----
 int pv_vec_run_block(pv_cache *c, hipStream_t s);        // pv_kernels_vector.hip
 int pv_mat_run_block(pv_cache *c, hipStream_t s);        // pv_kernels_matrix.hip
-int pv_mat_repack(const pv_model *m, const pv_tensor_ref &t, int64_t row_begin, int64_t row_count, hipStream_t s);
+int pv_mat_repack(const pv_model *m, const pv_tensor_ref &t, int kind, int64_t row_begin, int64_t row_count, hipStream_t s);
 size_t pv_mat_part_floats(const pv_model *m, int rows_cap);
 int pv_common_export(pv_cache *c, void *d_out, hipStream_t s);   // gathers logical K/V into d_out
 void pv_set_error(const char *fmt, ...);
