@@ -178,6 +178,20 @@ int pv_cache_export(pv_cache *c, void *host_out, size_t nbytes, void *hip_stream
  * weight once + K/V of length+gamma positions once + the K/V written. */
 int pv_step_bytes(const pv_cache *c, int32_t gamma, uint64_t *bytes);
 
+/* ---- instrumentation ---- */
+
+typedef enum {
+    PV_PROF_NONE = 0, PV_PROF_QKV = 1, PV_PROF_ATTENTION = 2, PV_PROF_OPROJ = 3, PV_PROF_GATEUP = 4,
+    PV_PROF_DOWN = 5, PV_PROF_LMHEAD = 6
+} pv_prof_kernel;
+
+/* Select one kernel of the step to be bracketed by HIP events on the step's own stream (every
+ * layer's launch of it, every following step) or switch that off.  Resets the counters. */
+int pv_profile_select(pv_cache *c, int32_t which);
+/* Sum of the bracketed durations (ms), number of launches, and the algorithmic bytes one launch
+ * streams (its weights; for attention the K/V of the current length).  Only between steps. */
+int pv_profile_read(pv_cache *c, double *total_ms, int64_t *launches, uint64_t *bytes_per_launch);
+
 const char *pv_strerror(int status);
 const char *pv_last_error(void);
 

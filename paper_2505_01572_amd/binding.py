@@ -9,6 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpipeverify.so")
 
 PV_F32, PV_BF16 = 0, 1
+PROF = {"none": 0, "qkv": 1, "attention": 2, "oproj": 3, "gateup": 4, "down": 5, "lmhead": 6}
 PATH_AUTO, PATH_VECTOR, PATH_MATRIX = 0, 1, 2
 KINDS = {"embed": 0, "attn_norm": 1, "wq": 2, "wk": 3, "wv": 4, "wo": 5,
          "ffn_norm": 6, "wg": 7, "wu": 8, "wd": 9, "final_norm": 10, "lm_head": 11}
@@ -33,6 +34,7 @@ EXPORTS = [
     "pv_cache_create", "pv_cache_destroy", "pv_cache_set_page_table", "pv_prefill", "pv_verify",
     "pv_verify_async", "pv_verify_wait", "pv_rollback", "pv_cache_len", "pv_cache_set_pending",
     "pv_debug_logits", "pv_debug_pred", "pv_cache_export", "pv_step_bytes", "pv_strerror", "pv_last_error",
+    "pv_profile_select", "pv_profile_read",
 ]
 
 _lib = None
@@ -67,6 +69,8 @@ def lib():
         L.pv_debug_pred.argtypes = [vp, vp, P(i32), vp]
         L.pv_cache_export.argtypes = [vp, vp, sz, vp]
         L.pv_step_bytes.argtypes = [vp, i32, P(ctypes.c_uint64)]
+        L.pv_profile_select.argtypes = [vp, i32]
+        L.pv_profile_read.argtypes = [vp, P(ctypes.c_double), P(i64), P(ctypes.c_uint64)]
         L.pv_strerror.argtypes = [ctypes.c_int]; L.pv_strerror.restype = ctypes.c_char_p
         L.pv_last_error.argtypes = []; L.pv_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -230,6 +234,14 @@ class Cache:
         b = ctypes.c_uint64()
         _check(self.L.pv_step_bytes(self.h, gamma, ctypes.byref(b)), "pv_step_bytes")
         return b.value
+
+    def profile_select(self, which):
+        _check(self.L.pv_profile_select(self.h, which), "pv_profile_select")
+
+    def profile_read(self):
+        ms, n, b = ctypes.c_double(), ctypes.c_int64(), ctypes.c_uint64()
+        _check(self.L.pv_profile_read(self.h, ctypes.byref(ms), ctypes.byref(n), ctypes.byref(b)), "pv_profile_read")
+        return ms.value, n.value, b.value
 
     def close(self):
         if self.h:

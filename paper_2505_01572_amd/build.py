@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpipeverify.so")
-SOURCES = ["pv_api.hip", "pv_kernels_common.hip", "pv_kernels_vector.hip", "pv_kernels_matrix.hip"]
+SOURCES = ["pv_api.hip", "pv_kernels_common.hip", "pv_kernels_vector.hip", "pv_kernels_matrix.hip", "pv_kernels_attention.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]

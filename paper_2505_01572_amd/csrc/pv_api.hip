@@ -59,8 +59,8 @@ static int check_config(const pv_model_config *c)
     if (c->d_model % 4 || c->ffn_dim % 4 || qd % 4) { pv_set_error("d_model, ffn_dim, q_dim must be multiples of 4"); return PV_EINVAL; }
     if (path == PV_PATH_MATRIX) {
         if (c->dtype != PV_BF16) { pv_set_error("matrix path needs bf16 storage"); return PV_EINVAL; }
-        if (c->d_model % 32 || c->ffn_dim % 32 || qd % 32 || c->vocab % 16 || c->head_dim % 16 || c->page_tokens < 16) {
-            pv_set_error("matrix path: d_model, ffn_dim, q_dim %% 32, vocab, head_dim %% 16, page_tokens >= 16 required");
+        if (c->d_model % 32 || c->ffn_dim % 32 || qd % 32 || c->vocab % 16 || (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) || c->page_tokens < 16) {
+            pv_set_error("matrix path: d_model, ffn_dim, q_dim %% 32, vocab %% 16, head_dim in {32, 64, 128}, page_tokens >= 16 required");
             return PV_EINVAL;
         }
     }
@@ -227,7 +227,7 @@ static size_t layout_ws(const pv_model *m, int rows_cap, int n_pages, pv_ws *w, 
     p = take(4 * R * c.ffn_dim); if (w) w->gate = (float *)p;
     p = take(4 * R * c.ffn_dim); if (w) w->up = (float *)p;
     p = take(4 * R * (size_t)c.vocab); if (w) w->logits = (float *)p;
-    const size_t pf = m->path == PV_PATH_MATRIX ? pv_mat_part_floats(m, rows_cap) : 0;
+    const size_t pf = m->path == PV_PATH_MATRIX ? pv_mat_part_floats(m, rows_cap, n_pages * m->cfg.page_tokens) : 0;
     p = take(4 * pf + 256); if (w) { w->part = (float *)p; w->part_floats = pf; }
     return off;
 }
@@ -262,12 +262,15 @@ extern "C" int pv_cache_create(const pv_model *m, void *d_page_pool, size_t page
     c->rows_cap = rows_cap_of(m);
     layout_ws(m, c->rows_cap, c->n_pages, &c->ws, c->d_ws);
     c->len = 0; c->pending = -1; c->last_rows = 0; c->in_flight = false; c->flight_stream = nullptr; c->io = nullptr;
+    c->prof_kind = PV_PROF_NONE; c->prof_pending = 0; c->prof_ev = nullptr; c->prof_ms = 0; c->prof_launches = 0;
     if (hipHostMalloc((void **)&c->io, sizeof(pv_host_io), hipHostMallocDefault) != hipSuccess) {
         pv_set_error("hipHostMalloc failed"); delete c; return PV_EHIP;
     }
     memset(c->io, 0, sizeof(pv_host_io));
     // device state, identity page table; activations zeroed once so padding rows are finite
+    // pages start out as zeros so that never-written slots of a page can never hold NaN bit patterns
     hipError_t e = hipMemset(c->d_ws, 0, need_w);
+    if (e == hipSuccess) e = hipMemset(c->d_pool, 0, need_p);
     int32_t *ident = (int32_t *)malloc(sizeof(int32_t) * c->n_pages);
     for (int i = 0; i < c->n_pages; ++i) ident[i] = i;
     if (e == hipSuccess) e = hipMemcpy(c->ws.page_table, ident, sizeof(int32_t) * c->n_pages, hipMemcpyHostToDevice);
@@ -283,6 +286,10 @@ extern "C" void pv_cache_destroy(pv_cache *c)
 {
     if (!c) return;
     if (c->io) (void)hipHostFree(c->io);
+    if (c->prof_ev) {
+        for (int i = 0; i < 2 * c->m->cfg.n_layers; ++i) (void)hipEventDestroy(c->prof_ev[i]);
+        free(c->prof_ev);
+    }
     delete c;
 }
 
@@ -323,8 +330,64 @@ static int enqueue_block(pv_cache *c, const int32_t *tokens, int rows, int mode,
     return PV_OK;
 }
 
+int pv_prof_mark(pv_cache *c, int kind, int slot, int end, hipStream_t s)
+{
+    if (c->prof_kind != kind) return PV_OK;
+    PV_HIP(hipEventRecord(c->prof_ev[2 * slot + end], s));
+    if (end && slot + 1 > c->prof_pending) c->prof_pending = slot + 1;
+    return PV_OK;
+}
+
+// after the step's stream has been synchronised: fold the event pairs into the counters
+static void prof_collect(pv_cache *c)
+{
+    for (int i = 0; i < c->prof_pending; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]) == hipSuccess) { c->prof_ms += ms; c->prof_launches += 1; }
+    }
+    c->prof_pending = 0;
+}
+
+extern "C" int pv_profile_select(pv_cache *c, int32_t which)
+{
+    if (!c) { pv_set_error("null cache"); return PV_EINVAL; }
+    if (c->in_flight) { pv_set_error("a verify is in flight on this cache"); return PV_ESTATE; }
+    if (which < PV_PROF_NONE || which > PV_PROF_LMHEAD) { pv_set_error("bad kernel selector %d", which); return PV_EINVAL; }
+    if (which != PV_PROF_NONE && !c->prof_ev) {
+        const int n = 2 * c->m->cfg.n_layers;
+        c->prof_ev = (hipEvent_t *)calloc(n, sizeof(hipEvent_t));
+        if (!c->prof_ev) return PV_ENOMEM;
+        for (int i = 0; i < n; ++i) PV_HIP(hipEventCreate(&c->prof_ev[i]));
+    }
+    c->prof_kind = which; c->prof_pending = 0; c->prof_ms = 0; c->prof_launches = 0;
+    return PV_OK;
+}
+
+extern "C" int pv_profile_read(pv_cache *c, double *total_ms, int64_t *launches, uint64_t *bytes_per_launch)
+{
+    if (!c) { pv_set_error("null cache"); return PV_EINVAL; }
+    if (c->in_flight) { pv_set_error("a verify is in flight on this cache"); return PV_ESTATE; }
+    const pv_model_config &f = c->m->cfg;
+    const uint64_t e = c->m->elt, d = f.d_model, qd = (uint64_t)f.n_q_heads * f.head_dim, kvd = (uint64_t)f.n_kv_heads * f.head_dim;
+    uint64_t b = 0;
+    switch (c->prof_kind) {
+    case PV_PROF_QKV: b = (qd + 2 * kvd) * d * e; break;
+    case PV_PROF_ATTENTION: b = 2 * kvd * e * (uint64_t)c->len; break;
+    case PV_PROF_OPROJ: b = d * qd * e; break;
+    case PV_PROF_GATEUP: b = 2 * (uint64_t)f.ffn_dim * d * e; break;
+    case PV_PROF_DOWN: b = (uint64_t)f.ffn_dim * d * e; break;
+    case PV_PROF_LMHEAD: b = (uint64_t)f.vocab * d * e; break;
+    default: break;
+    }
+    if (total_ms) *total_ms = c->prof_ms;
+    if (launches) *launches = c->prof_launches;
+    if (bytes_per_launch) *bytes_per_launch = b;
+    return PV_OK;
+}
+
 static void absorb_result(pv_cache *c)
 {
+    prof_collect(c);
     c->len += c->io->result[0];
     c->pending = c->io->result[1];
 }

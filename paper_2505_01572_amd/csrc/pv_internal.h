@@ -72,7 +72,15 @@ struct pv_cache {
     pv_host_io *io;             // pinned
     int32_t len, pending, last_rows;
     bool in_flight; hipStream_t flight_stream;
+    // instrumentation: one kernel kind bracketed by events, one pair per layer
+    int32_t prof_kind, prof_pending;
+    hipEvent_t *prof_ev;        // [2 * n_layers], created on first use
+    double prof_ms; int64_t prof_launches;
 };
+
+// bracket helper used by the kernel families: records the start/end event of slot `slot`
+// when `kind` is the selected kernel
+int pv_prof_mark(pv_cache *c, int kind, int slot, int end, hipStream_t s);
 
 static inline const pv_tensor_ref &pv_tref(const pv_model *m, int kind, int layer)
 {
@@ -82,9 +90,13 @@ static inline const pv_tensor_ref &pv_tref(const pv_model *m, int kind, int laye
 
 // KV page pool addressing, in elements:
 //   block(layer, phys_page, kv_head, which) = (((layer*n_pages + phys)*n_kv_heads + kv_head)*2 + which) * page_tokens*head_dim
-//   K block: [token][head_dim]      V block: [head_dim][token]   (V is kept transposed inside a page)
+// Inside a block, element (token t of the page, feature e):
+//   vector path  K: [t][e]                    V: [e][t]            (V transposed inside the page)
+//   matrix path  tokens grouped by 16 (one MFMA tile of keys), group s = t/16, u = t%16:
+//                K: [s][e/32][u + 16*((e%32)/8)][e%8]   -- each 16x32 sub-tile is an MFMA A operand
+//                V: [s][e][u]
 struct pv_kv_geom {
-    int32_t n_pages, n_kv_heads, page_tokens, head_dim, page_shift;
+    int32_t n_pages, n_kv_heads, page_tokens, head_dim, page_shift, tiled;
 };
 
 __host__ __device__ static inline size_t pv_kv_block(const pv_kv_geom &g, int layer, int phys, int kvh, int which)
@@ -92,11 +104,25 @@ __host__ __device__ static inline size_t pv_kv_block(const pv_kv_geom &g, int la
     return ((((size_t)layer * g.n_pages + phys) * g.n_kv_heads + kvh) * 2 + which) * (size_t)(g.page_tokens * g.head_dim);
 }
 
+__host__ __device__ static inline size_t pv_k_off(const pv_kv_geom &g, int t, int e)
+{
+    if (!g.tiled) return (size_t)t * g.head_dim + e;
+    return (size_t)(t >> 4) * 16 * g.head_dim + (size_t)(((e >> 5) * 64) + (t & 15) + 16 * ((e & 31) >> 3)) * 8 + (e & 7);
+}
+
+__host__ __device__ static inline size_t pv_v_off(const pv_kv_geom &g, int t, int e)
+{
+    if (!g.tiled) return (size_t)e * g.page_tokens + t;
+    return (size_t)(t >> 4) * 16 * g.head_dim + (size_t)e * 16 + (t & 15);
+}
+
 // ---- kernel-family entry points (host functions that enqueue on `s`) ----
 int pv_vec_run_block(pv_cache *c, hipStream_t s);        // pv_kernels_vector.hip
 int pv_mat_run_block(pv_cache *c, hipStream_t s);        // pv_kernels_matrix.hip
 int pv_mat_repack(const pv_model *m, const pv_tensor_ref &t, int kind, int64_t row_begin, int64_t row_count, hipStream_t s);
-size_t pv_mat_part_floats(const pv_model *m, int rows_cap);
+size_t pv_mat_part_floats(const pv_model *m, int rows_cap, int max_tokens);
+size_t pv_attn_part_floats(const pv_model *m, int rows_cap, int max_tokens);
+int pv_mat_attention(pv_cache *c, int layer, int rows, float *part, uint16_t *xop_o, hipStream_t s);
 int pv_common_export(pv_cache *c, void *d_out, hipStream_t s);   // gathers logical K/V into d_out
 void pv_set_error(const char *fmt, ...);
 

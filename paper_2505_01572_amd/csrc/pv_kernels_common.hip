@@ -57,14 +57,14 @@ k_rope_append(const pv_dev_state *st, const int32_t *page_table, const float2 *r
         const int h = idx / half, i = idx - h * half;
         const float2 c = cs[i];
         const float a = kr[h * hd + i], b = kr[h * hd + i + half];
-        ST *kb = pool + pv_kv_block(g, layer, phys, h, 0) + (size_t)tok * hd;
-        pv_st(kb, i, a * c.x - b * c.y);
-        pv_st(kb, i + half, b * c.x + a * c.y);
+        ST *kb = pool + pv_kv_block(g, layer, phys, h, 0);
+        pv_st(kb, pv_k_off(g, tok, i), a * c.x - b * c.y);
+        pv_st(kb, pv_k_off(g, tok, i + half), b * c.x + a * c.y);
     }
     for (int idx = threadIdx.x; idx < g.n_kv_heads * hd; idx += 256) {
         const int h = idx / hd, e = idx - h * hd;
         ST *vb = pool + pv_kv_block(g, layer, phys, h, 1);
-        pv_st(vb, (size_t)e * g.page_tokens + tok, vr[h * hd + e]);
+        pv_st(vb, pv_v_off(g, tok, e), vr[h * hd + e]);
     }
 }
 
@@ -151,7 +151,7 @@ __global__ void k_export(const ST *pool, const int32_t *page_table, pv_kv_geom g
     const int h = c / g.head_dim, d = c - h * g.head_dim;
     const int phys = page_table[pos >> g.page_shift], tok = pos & (g.page_tokens - 1);
     const ST *b = pool + pv_kv_block(g, layer, phys, h, which);
-    out[i] = which ? b[(size_t)d * g.page_tokens + tok] : b[(size_t)tok * g.head_dim + d];
+    out[i] = which ? b[pv_v_off(g, tok, d)] : b[pv_k_off(g, tok, d)];
 }
 
 // ------------------------------- host launchers ----------------------------------------
@@ -161,6 +161,7 @@ pv_kv_geom pv_geom(const pv_cache *c)
     pv_kv_geom g;
     g.n_pages = c->n_pages; g.n_kv_heads = c->m->cfg.n_kv_heads; g.page_tokens = c->m->cfg.page_tokens;
     g.head_dim = c->m->cfg.head_dim;
+    g.tiled = c->m->path == PV_PATH_MATRIX;
     g.page_shift = 0;
     while ((1 << g.page_shift) < g.page_tokens) ++g.page_shift;
     return g;

@@ -19,10 +19,8 @@
 // commutes with the contraction.  Rows of W_q/W_k are permuted inside each head so that the two
 // members of a rotary pair sit in the same strip 8 rows apart (lanes l and l^32 of the
 // accumulator); gate and up rows are interleaved the same way for SwiGLU.
-#include "pv_kernels_common.h"
+#include "pv_matrix_common.h"
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
 
@@ -30,12 +28,14 @@ struct mat_ws {                 // carved out of pv_ws::part
     uint16_t *xop_a, *xop_o, *xop_f, *xop_d;   // operands: QKV in (K=d), O in (K=qd), gate/up in (K=d), down in (K=F)
     float *ssq0, *ssq1;                         // [d/16][16] partial sums of x^2
     float *pmax_val; int32_t *pmax_idx;         // [vocab/16][16] per-strip arg-max candidates
+    float *attn_part;                           // attention chunk partials
 };
 
 static inline size_t xop_elems(int K) { return (size_t)2 * (K / 32) * 512; }   // hi and lo arrays
 
-static size_t mat_ws_layout(const pv_model_config &f, float *base, mat_ws *w)
+static size_t mat_ws_layout(const pv_model *m, int rows_cap, int max_tokens, float *base, mat_ws *w)
 {
+    const pv_model_config &f = m->cfg;
     const int qd = f.n_q_heads * f.head_dim;
     size_t off = 0;   // in floats, every piece a multiple of 64 floats (256 B)
     auto take = [&](size_t floats) { size_t o = off; off += (floats + 63) / 64 * 64; return base ? base + o : (float *)nullptr; };
@@ -48,10 +48,11 @@ static size_t mat_ws_layout(const pv_model_config &f, float *base, mat_ws *w)
     p = take((size_t)f.d_model); if (w) w->ssq1 = p;
     p = take((size_t)f.vocab); if (w) w->pmax_val = p;
     p = take((size_t)f.vocab); if (w) w->pmax_idx = (int32_t *)p;
+    p = take(pv_attn_part_floats(m, rows_cap, max_tokens)); if (w) w->attn_part = p;
     return off;
 }
 
-size_t pv_mat_part_floats(const pv_model *m, int) { return mat_ws_layout(m->cfg, nullptr, nullptr); }
+size_t pv_mat_part_floats(const pv_model *m, int rows_cap, int max_tokens) { return mat_ws_layout(m, rows_cap, max_tokens, nullptr, nullptr); }
 
 // ------------------------------------------------------------------------------------------
 // Weight repack: rows [row_begin, row_begin+row_count) of one tensor, row-major in staging,
@@ -94,37 +95,11 @@ int pv_mat_repack(const pv_model *m, const pv_tensor_ref &t, int kind, int64_t r
     return PV_OK;
 }
 
-// ------------------------------------------------------------------------------------------
-// Operand writers.  Element (row j, K-index k) of an activation lives at
-//   arr[(k/32)*512 + (col + 16*((k%32)/8))*8 + k%8],  col = j (hi) / j+8 (lo) when NB == 1,
-//   and col = j in the hi array / lo array when NB == 2.
-// ------------------------------------------------------------------------------------------
-__device__ inline uint16_t bf16_rne(float f) { return pv_f32_to_bf16(f); }
-
-// four consecutive k (k0 % 4 == 0) of row j
-template <int NB>
-__device__ inline void store_operand4(uint16_t *xop, int K, int j, int k0, const float y[4])
-{
-    uint16_t hi[4], lo[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) { hi[r] = bf16_rne(y[r]); lo[r] = bf16_rne(y[r] - pv_bf16_to_f32(hi[r])); }
-    const size_t tile = (size_t)(k0 >> 5) * 512, in = (size_t)(((k0 & 31) >> 3) * 16) * 8 + (k0 & 7);
-    const uint2 vh = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
-    const uint2 vl = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
-    if (NB == 1) {
-        *(uint2 *)(xop + tile + in + (size_t)j * 8) = vh;
-        *(uint2 *)(xop + tile + in + (size_t)(j + 8) * 8) = vl;
-    } else {
-        *(uint2 *)(xop + tile + in + (size_t)j * 8) = vh;
-        *(uint2 *)(xop + (size_t)(K / 32) * 512 + tile + in + (size_t)j * 8) = vl;
-    }
-}
-
 // Shared tail of everything that produces a new residual stream value: store x, the partial
 // sum of squares of this 16-feature strip, and (gain * x) as the next GEMM's operand.
 // Lane layout: j = lane % 16 (row), g = lane / 16, features n0 + 4g + r.
 template <int NB>
-__device__ inline void emit_x(int lane, int rows, int strip, int d, const float v[4], const uint16_t *gain,
+__device__ inline void emit_x(int lane, int rows, int strip, int d, const float v[4], uint2 gain4,
                               float *x, float *ssq, uint16_t *xop)
 {
     const int j = lane & 15, g = lane >> 4, n = strip * 16 + 4 * g;
@@ -135,9 +110,8 @@ __device__ inline void emit_x(int lane, int rows, int strip, int d, const float 
     ss += __shfl_xor(ss, 32, 64);
     if (lane < 16) ssq[strip * 16 + j] = ss;
     if (live) {
-        float y[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) y[r] = v[r] * pv_bf16_to_f32(gain[n + r]);
+        const float y[4] = {v[0] * pv_bf16_to_f32((uint16_t)(gain4.x & 0xffffu)), v[1] * pv_bf16_to_f32((uint16_t)(gain4.x >> 16)),
+                            v[2] * pv_bf16_to_f32((uint16_t)(gain4.y & 0xffffu)), v[3] * pv_bf16_to_f32((uint16_t)(gain4.y >> 16))};
         store_operand4<NB>(xop, d, j, n, y);
     }
 }
@@ -156,7 +130,7 @@ k_mat_begin(const pv_dev_state *st, const uint16_t *embed, const uint16_t *gain,
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] = pv_bf16_to_f32(e[r]);
     }
-    emit_x<NB>(lane, rows, strip, d, v, gain, x, ssq, xop);
+    emit_x<NB>(lane, rows, strip, d, v, *(const uint2 *)(gain + strip * 16 + 4 * g), x, ssq, xop);
     for (int idx = blockIdx.x * 64 + lane; idx < rows * half; idx += gridDim.x * 64) {
         const int jj = idx / half, i = idx - jj * half;
         double sn, cs;
@@ -198,9 +172,31 @@ struct gemm_args {
     float *logits; float *pmax_val; int32_t *pmax_idx; int vocab;
 };
 
-__device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c)
+
+// rsqrt(mean(x_j^2) + eps) for row j = lane % 16 from the [parts][16] partial sums, summed in a
+// fixed order.  All loads are independent (a serial chain of L2 round trips would cost far more
+// than the weight stream it sits beside): lane l reads float4 number l, l+64, ... so it always
+// sees rows 4*(l%4)..+3; lanes with equal l%4 are then combined and the result redistributed.
+__device__ inline float row_rscale(const float *ssq, int parts, float inv_d, float eps, int lane)
 {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    const float4 *q = (const float4 *)ssq;
+    const int n4 = parts * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i0 = lane; i0 < n4; i0 += 64 * 8) {
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { const int i = i0 + u * 64; v[u] = i < n4 ? q[i] : make_float4(0.f, 0.f, 0.f, 0.f); }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+    }
+#pragma unroll
+    for (int o = 4; o <= 32; o <<= 1) {
+        s.x += __shfl_xor(s.x, o, 64); s.y += __shfl_xor(s.y, o, 64); s.z += __shfl_xor(s.z, o, 64); s.w += __shfl_xor(s.w, o, 64);
+    }
+    const int j = lane & 15, src = j >> 2;
+    const float t0 = __shfl(s.x, src, 64), t1 = __shfl(s.y, src, 64), t2 = __shfl(s.z, src, 64), t3 = __shfl(s.w, src, 64);
+    const float tot = (j & 3) == 0 ? t0 : (j & 3) == 1 ? t1 : (j & 3) == 2 ? t2 : t3;
+    return 1.0f / sqrtf(tot * inv_d + eps);
 }
 
 template <int NB, int EPI>
@@ -208,6 +204,7 @@ __global__ void __launch_bounds__(512)
 k_gemm(const gemm_args a)
 {
     constexpr int U = 4;
+    constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
     const int strip = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int KT = a.ktiles, per = (KT + 7) >> 3;
     const int kb = wave * per, ke = min(KT, kb + per);
@@ -216,27 +213,49 @@ k_gemm(const gemm_args a)
     const uint4 *B2 = a.xop + (size_t)KT * 64 + lane;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 
+    // The owner wave fetches what its epilogue needs before streaming, so that after the
+    // reduction only arithmetic and stores remain: rsqrt(mean(x^2)+eps) of its row.
+    float rj = 1.f;
+    int rows = 0, pos = 0, phys = 0;
+    float4 xo = make_float4(0.f, 0.f, 0.f, 0.f);
+    uint2 gn = make_uint2(0u, 0u);
+    float2 cs[4] = {make_float2(1.f, 0.f), make_float2(1.f, 0.f), make_float2(1.f, 0.f), make_float2(1.f, 0.f)};
+    if (wave == 0) {
+        const int j = lane & 15, g = lane >> 4;
+        rows = a.st->gamma;
+        if (NORM) rj = row_rscale(a.ssq, a.ssq_parts, a.inv_d, a.eps, lane);
+        if (EPI == EPI_RESID) {
+            const int n = strip * 16 + 4 * g;
+            if (j < rows) xo = *(const float4 *)(a.x + (size_t)j * a.d + n);
+            gn = *(const uint2 *)(a.gain_next + n);
+        }
+        if (EPI == EPI_QKV) {
+            pos = a.st->len + j;
+            if (j < rows) {
+                if (strip >= a.q_strips) phys = a.page_table[pos >> a.geom.page_shift];
+                if (strip < a.q_strips + a.k_strips) {
+                    const int spH = a.geom.head_dim >> 4, tt = strip % spH, e = tt * 8 + 4 * (g & 1);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) cs[r] = a.rope[(size_t)j * (a.geom.head_dim >> 1) + e + r];
+                }
+            }
+        }
+    }
+
+    // Few registers on purpose: latency is hidden by many resident workgroups per CU.
     int t = kb;
-    if (t + U <= ke) {
-        uint4 a0[U], b0[U], c0[U], a1[U], b1[U], c1[U];
-#define PV_LOAD(A_, B_, C_)                                                                   \
-        _Pragma("unroll") for (int u = 0; u < U; ++u) {                                       \
-            A_[u] = A[(size_t)(t + u) * 64]; B_[u] = B[(size_t)(t + u) * 64];                 \
-            if (NB == 2) C_[u] = B2[(size_t)(t + u) * 64];                                    \
-        }                                                                                     \
-        t += U;
-#define PV_MMA(A_, B_, C_)                                                                    \
-        _Pragma("unroll") for (int u = 0; u < U; ++u) {                                       \
-            acc = mfma16(A_[u], B_[u], acc);                                                  \
-            if (NB == 2) acc = mfma16(A_[u], C_[u], acc);                                     \
+    for (; t + U <= ke; t += U) {
+        uint4 ra[U], rb[U], rc[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            ra[u] = A[(size_t)(t + u) * 64]; rb[u] = B[(size_t)(t + u) * 64];
+            if (NB == 2) rc[u] = B2[(size_t)(t + u) * 64];
         }
-        PV_LOAD(a0, b0, c0)
-        for (;;) {                       // two register buffers: loads of one overlap the MFMAs of the other
-            if (t + U <= ke) { PV_LOAD(a1, b1, c1) PV_MMA(a0, b0, c0) } else { PV_MMA(a0, b0, c0) break; }
-            if (t + U <= ke) { PV_LOAD(a0, b0, c0) PV_MMA(a1, b1, c1) } else { PV_MMA(a1, b1, c1) break; }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            acc = mfma16(ra[u], rb[u], acc);
+            if (NB == 2) acc = mfma16(ra[u], rc[u], acc);
         }
-#undef PV_LOAD
-#undef PV_MMA
     }
     for (; t < ke; ++t) {
         acc = mfma16(A[(size_t)t * 64], B[(size_t)t * 64], acc);
@@ -252,18 +271,13 @@ k_gemm(const gemm_args a)
 #pragma unroll
     for (int w = 1; w < 8; ++w) { const f32x4 p = red[w][lane]; sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3]; }
 
-    const int j = lane & 15, g = lane >> 4, rows = a.st->gamma;
+    const int j = lane & 15, g = lane >> 4;
     float v[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) v[r] = (NB == 1) ? sum[r] + __shfl_down(sum[r], 8, 64) : sum[r];
     const bool live = j < rows;          // NB == 1 implies rows <= 8, so live lanes hold the combined value
 
-    if (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD) {
-        float s = 0.f;
-        for (int p = g; p < a.ssq_parts; p += 4) s += a.ssq[p * 16 + j];
-        s += __shfl_xor(s, 16, 64);
-        s += __shfl_xor(s, 32, 64);
-        const float rj = 1.0f / sqrtf(s * a.inv_d + a.eps);
+    if (NORM) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] *= rj;
     }
@@ -271,39 +285,34 @@ k_gemm(const gemm_args a)
     if (EPI == EPI_QKV) {
         const pv_kv_geom &gm = a.geom;
         const int hd = gm.head_dim, half = hd >> 1, spH = hd >> 4;
-        const int pos = a.st->len + j;
         if (strip < a.q_strips + a.k_strips) {
             const int h = strip / spH, tt = strip - h * spH, side = g >> 1, e = tt * 8 + 4 * (g & 1);
             float o[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float partner = __shfl_xor(v[r], 32, 64);
-                const float2 cs = live ? a.rope[(size_t)j * half + e + r] : make_float2(1.f, 0.f);
-                o[r] = side ? v[r] * cs.x + partner * cs.y : v[r] * cs.x - partner * cs.y;
+                o[r] = side ? v[r] * cs[r].x + partner * cs[r].y : v[r] * cs[r].x - partner * cs[r].y;
             }
             if (live) {
                 if (strip < a.q_strips) {
                     *(float4 *)(a.q + ((size_t)j * a.n_q_heads + h) * hd + e + side * half) = make_float4(o[0], o[1], o[2], o[3]);
                 } else {
                     const int kvh = h - a.n_q_heads;
-                    const int phys = a.page_table[pos >> gm.page_shift], tok = pos & (gm.page_tokens - 1);
-                    uint16_t *kp = a.pool + pv_kv_block(gm, a.layer, phys, kvh, 0) + (size_t)tok * hd + e + side * half;
+                    const int tok = pos & (gm.page_tokens - 1);
+                    uint16_t *kp = a.pool + pv_kv_block(gm, a.layer, phys, kvh, 0) + pv_k_off(gm, tok, e + side * half);
                     *(uint2 *)kp = make_uint2(bf16_rne(o[0]) | ((uint32_t)bf16_rne(o[1]) << 16), bf16_rne(o[2]) | ((uint32_t)bf16_rne(o[3]) << 16));
                 }
             }
         } else if (live) {
             const int sv = strip - a.q_strips - a.k_strips, kvh = sv / spH, e = (sv - kvh * spH) * 16 + 4 * g;
-            const int phys = a.page_table[pos >> gm.page_shift], tok = pos & (gm.page_tokens - 1);
-            uint16_t *vp = a.pool + pv_kv_block(gm, a.layer, phys, kvh, 1) + tok;
+            const int tok = pos & (gm.page_tokens - 1);
+            uint16_t *vp = a.pool + pv_kv_block(gm, a.layer, phys, kvh, 1);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) vp[(size_t)(e + r) * gm.page_tokens] = bf16_rne(v[r]);
+            for (int r = 0; r < 4; ++r) vp[pv_v_off(gm, tok, e + r)] = bf16_rne(v[r]);
         }
     } else if (EPI == EPI_RESID) {
-        if (live) {
-            const float4 xo = *(const float4 *)(a.x + (size_t)j * a.d + strip * 16 + 4 * g);
-            v[0] += xo.x; v[1] += xo.y; v[2] += xo.z; v[3] += xo.w;
-        }
-        emit_x<NB>(lane, rows, strip, a.d, v, a.gain_next, a.x, a.ssq_out, a.xop_out);
+        v[0] += xo.x; v[1] += xo.y; v[2] += xo.z; v[3] += xo.w;       // xo is zero on dead lanes
+        emit_x<NB>(lane, rows, strip, a.d, v, gn, a.x, a.ssq_out, a.xop_out);
     } else if (EPI == EPI_SWIGLU) {
         float act[4];
 #pragma unroll
@@ -366,7 +375,7 @@ static int run_block(pv_cache *c, hipStream_t s)
     const pv_model_config &f = m->cfg;
     const int rows = c->last_rows, d = f.d_model, hd = f.head_dim, qd = f.n_q_heads * hd, kvd = f.n_kv_heads * hd, F = f.ffn_dim;
     mat_ws mw;
-    mat_ws_layout(f, c->ws.part, &mw);
+    mat_ws_layout(m, c->rows_cap, c->n_pages * f.page_tokens, c->ws.part, &mw);
     const char *Wb = m->d_weights;
     auto gainp = [&](int kind, int l) { return (const uint16_t *)(Wb + pv_tref(m, kind, l).off); };
 
@@ -375,6 +384,7 @@ static int run_block(pv_cache *c, hipStream_t s)
     PV_HIP(hipGetLastError());
 
     gemm_args g = {};
+    int prc;
     g.st = c->ws.state; g.inv_d = 1.0f / (float)d; g.eps = (float)f.rms_eps; g.ssq_parts = d / 16;
     g.q = c->ws.q; g.pool = (uint16_t *)c->d_pool; g.page_table = c->ws.page_table; g.rope = c->ws.rope; g.geom = pv_geom(c);
     g.n_q_heads = f.n_q_heads; g.q_strips = qd / 16; g.k_strips = kvd / 16;
@@ -385,35 +395,45 @@ static int run_block(pv_cache *c, hipStream_t s)
         // fused QKV projection: RMSNorm scale, rotary embedding, KV append
         g.W = (const uint4 *)(Wb + pv_tref(m, PV_T_WQ, l).off); g.xop = (const uint4 *)mw.xop_a; g.ktiles = d / 32;
         g.ssq = mw.ssq0; g.layer = l;
+        if ((prc = pv_prof_mark(c, PV_PROF_QKV, l, 0, s)) != PV_OK) return prc;
         k_gemm<NB, EPI_QKV><<<(qd + 2 * kvd) / 16, 512, 0, s>>>(g);
         PV_HIP(hipGetLastError());
-        // attention (vector kernel for now) -> operand of the output projection
-        int rc = pv_vec_attention_bf16(c, l, rows, s);
+        if ((prc = pv_prof_mark(c, PV_PROF_QKV, l, 1, s)) != PV_OK) return prc;
+        // attention over the paged cache -> operand of the output projection
+        if ((prc = pv_prof_mark(c, PV_PROF_ATTENTION, l, 0, s)) != PV_OK) return prc;
+        int rc = pv_mat_attention(c, l, rows, mw.attn_part, mw.xop_o, s);
         if (rc != PV_OK) return rc;
-        k_to_operand<NB><<<(rows * (qd / 4) + 255) / 256, 256, 0, s>>>(c->ws.state, c->ws.attn, mw.xop_o, qd);
-        PV_HIP(hipGetLastError());
+        if ((prc = pv_prof_mark(c, PV_PROF_ATTENTION, l, 1, s)) != PV_OK) return prc;
         // output projection + residual; emits the FFN operand and sum of squares
         g.W = (const uint4 *)(Wb + pv_tref(m, PV_T_WO, l).off); g.xop = (const uint4 *)mw.xop_o; g.ktiles = qd / 32;
         g.gain_next = gainp(PV_T_FFN_NORM, l); g.ssq_out = mw.ssq1; g.xop_out = mw.xop_f;
+        if ((prc = pv_prof_mark(c, PV_PROF_OPROJ, l, 0, s)) != PV_OK) return prc;
         k_gemm<NB, EPI_RESID><<<d / 16, 512, 0, s>>>(g);
         PV_HIP(hipGetLastError());
+        if ((prc = pv_prof_mark(c, PV_PROF_OPROJ, l, 1, s)) != PV_OK) return prc;
         // gate/up projection + SwiGLU
         g.W = (const uint4 *)(Wb + pv_tref(m, PV_T_WG, l).off); g.xop = (const uint4 *)mw.xop_f; g.ktiles = d / 32;
         g.ssq = mw.ssq1;
+        if ((prc = pv_prof_mark(c, PV_PROF_GATEUP, l, 0, s)) != PV_OK) return prc;
         k_gemm<NB, EPI_SWIGLU><<<F / 8, 512, 0, s>>>(g);
         PV_HIP(hipGetLastError());
+        if ((prc = pv_prof_mark(c, PV_PROF_GATEUP, l, 1, s)) != PV_OK) return prc;
         // down projection + residual; emits the next layer's (or the head's) operand
         g.W = (const uint4 *)(Wb + pv_tref(m, PV_T_WD, l).off); g.xop = (const uint4 *)mw.xop_d; g.ktiles = F / 32;
         g.gain_next = (l + 1 < f.n_layers) ? gainp(PV_T_ATTN_NORM, l + 1) : (const uint16_t *)(Wb + m->global[PV_T_FINAL_NORM].off);
         g.ssq_out = mw.ssq0; g.xop_out = mw.xop_a;
+        if ((prc = pv_prof_mark(c, PV_PROF_DOWN, l, 0, s)) != PV_OK) return prc;
         k_gemm<NB, EPI_RESID><<<d / 16, 512, 0, s>>>(g);
         PV_HIP(hipGetLastError());
+        if ((prc = pv_prof_mark(c, PV_PROF_DOWN, l, 1, s)) != PV_OK) return prc;
     }
     const bool head = c->io->hdr[3] != PV_MODE_PREFILL_MID;
     if (head) {
         g.W = (const uint4 *)(Wb + m->global[PV_T_LM_HEAD].off); g.xop = (const uint4 *)mw.xop_a; g.ktiles = d / 32; g.ssq = mw.ssq0;
+        if ((prc = pv_prof_mark(c, PV_PROF_LMHEAD, 0, 0, s)) != PV_OK) return prc;
         k_gemm<NB, EPI_LMHEAD><<<f.vocab / 16, 512, 0, s>>>(g);
         PV_HIP(hipGetLastError());
+        if ((prc = pv_prof_mark(c, PV_PROF_LMHEAD, 0, 1, s)) != PV_OK) return prc;
         k_argmax_parts<<<rows, 256, 0, s>>>(c->ws.state, mw.pmax_val, mw.pmax_idx, f.vocab / 16);
         PV_HIP(hipGetLastError());
     }

@@ -104,9 +104,10 @@ k_attention(const pv_dev_state *st, const int32_t *page_table, const float *q, c
         float lm = -INFINITY;
         for (int t = threadIdx.x; t < cn; t += 256) {
             const int p = c0 + t;
-            const ST *kb = pool + pv_kv_block(g, layer, page_table[p >> g.page_shift], kvh, 0) + (size_t)(p & (g.page_tokens - 1)) * hd;
+            const ST *kb = pool + pv_kv_block(g, layer, page_table[p >> g.page_shift], kvh, 0);
+            const int tk = p & (g.page_tokens - 1);
             float s = 0.f;
-            for (int e = 0; e < hd; ++e) s += qs[e] * pv_ld(kb, e);
+            for (int e = 0; e < hd; ++e) s += qs[e] * pv_ld(kb, pv_k_off(g, tk, e));
             s *= scale;
             sc[t] = s;
             lm = fmaxf(lm, s);
@@ -122,7 +123,7 @@ k_attention(const pv_dev_state *st, const int32_t *page_table, const float *q, c
             for (int t = 0; t < cn; ++t) {
                 const int p = c0 + t;
                 const ST *vb = pool + pv_kv_block(g, layer, page_table[p >> g.page_shift], kvh, 1);
-                acc += sc[t] * pv_ld(vb, (size_t)threadIdx.x * g.page_tokens + (p & (g.page_tokens - 1)));
+                acc += sc[t] * pv_ld(vb, pv_v_off(g, p & (g.page_tokens - 1), threadIdx.x));
             }
             o = o * resc + acc;
         }

@@ -88,7 +88,7 @@ def quantile_table(dtype: str, sigma: float = 0.02):
 
 
 def fill_tensor(m: ModelShape, kind: str, layer: int, start: int = 0, count: int = None,
-                gains: str = "ones", use_c: bool = True):
+                gains: str = "ones", use_c: bool = True, out=None):
     """Flat slice [start, start+count) of one tensor in storage type (uint16 bf16 bits or float32).
 
     Norm gains are 1.0 ("ones") or 1 + N(0, 0.02^2) draws ("perturbed", used by tests so that a
@@ -105,7 +105,11 @@ def fill_tensor(m: ModelShape, kind: str, layer: int, start: int = 0, count: int
         one = np.float32(1.0)
         return (np.full(count, bf16_round_f32(np.array([one]))[0], dtype=np.uint16)
                 if m.dtype == "bf16" else np.full(count, one, dtype=np.float32))
-    out = np.empty(count, dtype=table.dtype)
+    if out is None:
+        out = np.empty(count, dtype=table.dtype)
+    else:                       # caller-owned scratch (reused between calls: no fresh page faults)
+        assert out.dtype == table.dtype and out.size >= count and out.flags.c_contiguous
+        out = out.reshape(-1)[:count]
     lib = _load() if use_c else None
     if lib is not None:
         rc = lib.pvs_fill_table(m.seed, tensor_id(kind, layer), start, count,
@@ -153,10 +157,15 @@ def perturb_drafts(tokens, alpha: float, vocab: int, seed: int, step: int):
     return np.where(u < (1.0 - alpha), r, tokens).astype(np.int32)
 
 
-def iter_row_chunks(m: ModelShape, kind: str, layer: int, max_rows: int, gains: str = "ones"):
-    """Yield (row_begin, rows[row_count, in_features]) pieces of one tensor, at most max_rows rows each."""
+def iter_row_chunks(m: ModelShape, kind: str, layer: int, max_rows: int, gains: str = "ones", scratch=None):
+    """Yield (row_begin, rows[row_count, in_features]) pieces of one tensor, at most max_rows rows each.
+
+    With `scratch` (a flat array of the storage type, >= max_rows * in_features elements) every
+    piece is written into that same buffer, so a piece is only valid until the next one is drawn."""
     shape = tensor_shape(m, kind)
     rows, cols = (1, shape[0]) if len(shape) == 1 else shape
+    is_gain = len(shape) == 1
     for r0 in range(0, rows, max_rows):
         n = min(max_rows, rows - r0)
-        yield r0, fill_tensor(m, kind, layer, start=r0 * cols, count=n * cols, gains=gains).reshape(n, cols)
+        buf = None if (scratch is None or is_gain) else scratch
+        yield r0, fill_tensor(m, kind, layer, start=r0 * cols, count=n * cols, gains=gains, out=buf).reshape(n, cols)
