@@ -2,10 +2,10 @@
 //
 // Work unit: one workgroup = (kv head, chunk of 256 keys, group of <= 32 query rows).  The
 // query rows of a kv head are its `group` query heads x gamma block rows, packed densely
-// (row m = head_in_group * gamma + j).  Each of the 4 wavefronts takes 64 keys in two steps of
-// 32; the four partial results are merged through LDS in wave order and written as one
-// partial (max, sum, output) per chunk; a small merge kernel combines the chunks and writes
-// the attention output directly as the output projection's split-bf16 operand.
+// (row m = head_in_group * gamma + j).  Each of the 8 wavefronts takes 32 keys; the eight
+// partial results are merged through LDS in a fixed order and written as one partial (max,
+// sum, output) per chunk; a small merge kernel combines the chunks and writes the attention
+// output directly as the output projection's split-bf16 operand.
 //
 // Everything is computed transposed so that no register shuffling is needed:
 //   S^T (keys x rows) = K (keys x hd) * Q^T (hd x rows)      A = K tile, B = Q^T
@@ -47,7 +47,7 @@ __device__ inline void split8(const float v[8], uint4 &hi, uint4 &lo)
 }
 
 template <int HD, int R>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(512)
 k_attn(const attn_args a)
 {
     constexpr int KS = HD / 32, ET = HD / 16, OS = HD + 1;
@@ -59,27 +59,24 @@ k_attn(const attn_args a)
     const pv_kv_geom &gm = a.geom;
     const int sub_shift = gm.page_shift - 4, sub_mask = (1 << sub_shift) - 1;
 
-    // Q^T operands of this lane's rows (row = lane%16 of each 16-row tile), hi and lo
-    uint4 qh[R][KS], ql[R][KS];
-    int lim[R];
+    // this wave's 32 keys: two groups of 16; a group past the end re-reads the first one (it is masked)
+    const int p0 = c * 256 + wave * 32;
+    const bool has_keys = p0 < nkeys;
+    uint4 kt[2][KS];
+    uint2 vt[2][ET];
+    if (has_keys) {
+        const int g0 = p0 >> 4, g1 = (p0 + 16 < nkeys) ? g0 + 1 : g0;
+        const int ph0 = a.page_table[g0 >> sub_shift], ph1 = a.page_table[g1 >> sub_shift];
+        const uint16_t *kb0 = a.pool + pv_kv_block(gm, a.layer, ph0, kvh, 0) + (size_t)(g0 & sub_mask) * 16 * HD;
+        const uint16_t *kb1 = a.pool + pv_kv_block(gm, a.layer, ph1, kvh, 0) + (size_t)(g1 & sub_mask) * 16 * HD;
+        const uint16_t *vb0 = a.pool + pv_kv_block(gm, a.layer, ph0, kvh, 1) + (size_t)(g0 & sub_mask) * 16 * HD;
+        const uint16_t *vb1 = a.pool + pv_kv_block(gm, a.layer, ph1, kvh, 1) + (size_t)(g1 & sub_mask) * 16 * HD;
 #pragma unroll
-    for (int rt = 0; rt < R; ++rt) {
-        const int m = mp * 32 + rt * 16 + jl;
-        const bool live = m < nrows;
-        const int al = live ? m / gamma : 0, j = live ? m - al * gamma : 0;
-        lim[rt] = live ? len + j : -1;
-        const float *qp = a.q + ((size_t)j * a.n_q_heads + kvh * a.group + al) * HD + g * 8;
+        for (int ks = 0; ks < KS; ++ks) { kt[0][ks] = ((const uint4 *)kb0)[ks * 64 + lane]; kt[1][ks] = ((const uint4 *)kb1)[ks * 64 + lane]; }
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            float v[8];
-            if (live) {
-                const float4 x0 = *(const float4 *)(qp + ks * 32), x1 = *(const float4 *)(qp + ks * 32 + 4);
-                v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[i] = 0.f;
-            }
-            split8(v, qh[rt][ks], ql[rt][ks]);
+        for (int et = 0; et < ET; ++et) {
+            vt[0][et] = *(const uint2 *)(vb0 + (size_t)(et * 16 + jl) * 16 + 4 * g);
+            vt[1][et] = *(const uint2 *)(vb1 + (size_t)(et * 16 + jl) * 16 + 4 * g);
         }
     }
 
@@ -92,63 +89,54 @@ k_attn(const attn_args a)
         for (int et = 0; et < ET; ++et) O[rt][et] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
 
-    const int k0 = c * 256 + wave * 64;
-    for (int step = 0; step < 2; ++step) {
-        const int p0 = k0 + step * 32;
-        if (p0 >= nkeys) break;
-        // two groups of 16 keys; the second may lie past the end: read the first again, it is masked
-        const int g0 = p0 >> 4, g1 = (p0 + 16 < nkeys) ? g0 + 1 : g0;
-        const uint16_t *kb[2], *vb[2];
-        {
-            const int ph0 = a.page_table[g0 >> sub_shift], ph1 = a.page_table[g1 >> sub_shift];
-            kb[0] = a.pool + pv_kv_block(gm, a.layer, ph0, kvh, 0) + (size_t)(g0 & sub_mask) * 16 * HD;
-            kb[1] = a.pool + pv_kv_block(gm, a.layer, ph1, kvh, 0) + (size_t)(g1 & sub_mask) * 16 * HD;
-            vb[0] = a.pool + pv_kv_block(gm, a.layer, ph0, kvh, 1) + (size_t)(g0 & sub_mask) * 16 * HD;
-            vb[1] = a.pool + pv_kv_block(gm, a.layer, ph1, kvh, 1) + (size_t)(g1 & sub_mask) * 16 * HD;
-        }
-        uint4 kt[2][KS];
-        uint2 vt[2][ET];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kt[t][ks] = ((const uint4 *)kb[t])[ks * 64 + lane];
-#pragma unroll
-            for (int et = 0; et < ET; ++et) vt[t][et] = *(const uint2 *)(vb[t] + (size_t)(et * 16 + jl) * 16 + 4 * g);
-        }
+    if (has_keys) {
 #pragma unroll
         for (int rt = 0; rt < R; ++rt) {
+            // Q^T operand of this lane's row (row = lane%16 of the 16-row tile), hi and lo
+            const int m = mp * 32 + rt * 16 + jl;
+            const bool live = m < nrows;
+            const int al = live ? m / gamma : 0, j = live ? m - al * gamma : 0;
+            const int lim = live ? len + j : -1;
+            const float *qp = a.q + ((size_t)j * a.n_q_heads + kvh * a.group + al) * HD + g * 8;
             f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                s0 = mfma16(kt[0][ks], qh[rt][ks], s0); s0 = mfma16(kt[0][ks], ql[rt][ks], s0);
-                s1 = mfma16(kt[1][ks], qh[rt][ks], s1); s1 = mfma16(kt[1][ks], ql[rt][ks], s1);
+                float v[8];
+                const float4 x0 = *(const float4 *)(qp + ks * 32), x1 = *(const float4 *)(qp + ks * 32 + 4);
+                v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+                if (!live) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = 0.f;
+                }
+                uint4 qh, ql;
+                split8(v, qh, ql);
+                s0 = mfma16(kt[0][ks], qh, s0); s0 = mfma16(kt[0][ks], ql, s0);
+                s1 = mfma16(kt[1][ks], qh, s1); s1 = mfma16(kt[1][ks], ql, s1);
             }
             float sv[8];
             float mx = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int pa = p0 + 4 * g + r, pb = pa + 16;
-                sv[r] = (pa <= lim[rt]) ? s0[r] * a.scale : -INFINITY;
-                sv[4 + r] = (pb <= lim[rt]) ? s1[r] * a.scale : -INFINITY;
+                sv[r] = (pa <= lim) ? s0[r] * a.scale : -INFINITY;
+                sv[4 + r] = (pb <= lim) ? s1[r] * a.scale : -INFINITY;
                 mx = fmaxf(mx, fmaxf(sv[r], sv[4 + r]));
             }
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(mrow[rt], mx);
-            const bool none = m_new == -INFINITY;              // no visible key for this row so far
-            const float resc = none ? 1.f : expf(mrow[rt] - m_new);
+            const bool none = mx == -INFINITY;                 // no visible key for this row here
             float pr[8], ps = 0.f;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) { pr[i] = none ? 0.f : expf(sv[i] - m_new); ps += pr[i]; }
-            lrow[rt] = lrow[rt] * resc + ps;
-            mrow[rt] = m_new;
+            for (int i = 0; i < 8; ++i) { pr[i] = none ? 0.f : expf(sv[i] - mx); ps += pr[i]; }
+            ps += __shfl_xor(ps, 16, 64);
+            ps += __shfl_xor(ps, 32, 64);
+            lrow[rt] = ps; mrow[rt] = mx;
             uint4 ph, pl;
             split8(pr, ph, pl);
 #pragma unroll
             for (int et = 0; et < ET; ++et) {
-                f32x4 o = O[rt][et];
-                o[0] *= resc; o[1] *= resc; o[2] *= resc; o[3] *= resc;
                 const uint4 va = make_uint4(vt[0][et].x, vt[0][et].y, vt[1][et].x, vt[1][et].y);
+                f32x4 o = {0.f, 0.f, 0.f, 0.f};
                 o = mfma16(va, ph, o);
                 o = mfma16(va, pl, o);
                 O[rt][et] = o;
@@ -156,25 +144,27 @@ k_attn(const attn_args a)
         }
     }
 
-    // merge the four waves (fixed order) and write the chunk's partial
-    __shared__ float sh_m[4][R * 16], sh_M[R * 16], sh_l[R * 16], sh_o[R * 16][OS];
+    // merge the eight waves in a fixed order: waves 0..3 into buffer 0, waves 4..7 into buffer 1
+    // (both sequences run side by side), then buffer 0 + buffer 1 while writing the partial
+    __shared__ float sh_m[8][R * 16], sh_M[R * 16], sh_l[2][R * 16], sh_o[2][R * 16][OS];
+    if (g == 0) {
 #pragma unroll
-    for (int rt = 0; rt < R; ++rt) {
-        lrow[rt] += __shfl_xor(lrow[rt], 16, 64);
-        lrow[rt] += __shfl_xor(lrow[rt], 32, 64);
-        if (g == 0) sh_m[wave][rt * 16 + jl] = mrow[rt];
+        for (int rt = 0; rt < R; ++rt) sh_m[wave][rt * 16 + jl] = mrow[rt];
     }
     __syncthreads();
     float f[R];
 #pragma unroll
     for (int rt = 0; rt < R; ++rt) {
         const int row = rt * 16 + jl;
-        const float M = fmaxf(fmaxf(sh_m[0][row], sh_m[1][row]), fmaxf(sh_m[2][row], sh_m[3][row]));
+        float M = sh_m[0][row];
+#pragma unroll
+        for (int w = 1; w < 8; ++w) M = fmaxf(M, sh_m[w][row]);
         f[rt] = (mrow[rt] == -INFINITY) ? 0.f : expf(mrow[rt] - M);
         if (wave == 0 && g == 0) sh_M[row] = M;
     }
+    const int half = wave >> 2, wq = wave & 3;
     for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
+        if (wq == w) {
 #pragma unroll
             for (int rt = 0; rt < R; ++rt) {
                 const int row = rt * 16 + jl;
@@ -183,45 +173,61 @@ k_attn(const attn_args a)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const float val = O[rt][et][r] * f[rt];
-                        float *dst = &sh_o[row][et * 16 + 4 * g + r];
+                        float *dst = &sh_o[half][row][et * 16 + 4 * g + r];
                         *dst = (w == 0) ? val : *dst + val;
                     }
-                if (g == 0) sh_l[row] = (w == 0) ? lrow[rt] * f[rt] : sh_l[row] + lrow[rt] * f[rt];
+                if (g == 0) sh_l[half][row] = (w == 0) ? lrow[rt] * f[rt] : sh_l[half][row] + lrow[rt] * f[rt];
             }
         }
         __syncthreads();
     }
     const size_t unit = ((size_t)kvh * gridDim.z + mp) * a.max_chunks + c;
     float *po = a.part_o + unit * 32 * HD;
-    for (int i = threadIdx.x; i < R * 16 * HD; i += 256) po[i] = sh_o[i / HD][i % HD];
+    for (int i = threadIdx.x; i < R * 16 * HD; i += 512) po[i] = sh_o[0][i / HD][i % HD] + sh_o[1][i / HD][i % HD];
     if (threadIdx.x < R * 16) {
         float *pm = a.part_ml + (unit * 32 + threadIdx.x) * 2;
-        pm[0] = sh_M[threadIdx.x]; pm[1] = sh_l[threadIdx.x];
+        pm[0] = sh_M[threadIdx.x]; pm[1] = sh_l[0][threadIdx.x] + sh_l[1][threadIdx.x];
     }
 }
 
 // Combine the chunk partials of one (block row, query head) and emit the operand of the
 // output projection.  One thread per 4 consecutive features.
 template <int NB, int HD>
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(256)
 k_attn_merge(const attn_args a, int mp_count)
 {
+    constexpr int TPC = HD / 4;            // threads per chunk: 4 consecutive features each
+    constexpr int NG = 256 / TPC;          // chunk groups working side by side
     const int j = blockIdx.x, aq = blockIdx.y, gamma = a.st->gamma;
     if (j >= gamma) return;
     const int kvh = aq / a.group, al = aq - kvh * a.group, m = al * gamma + j, mp = m >> 5, row = m & 31;
     const int nchunks = (a.st->len + gamma + 255) >> 8;
     const size_t unit0 = ((size_t)kvh * mp_count + mp) * a.max_chunks;
+    __shared__ float sh_m[256], sh_acc[NG][TPC][5];
+    // global max over chunks (each thread looks at chunks t, t+256, ...)
     float M = -INFINITY;
-    for (int c = 0; c < nchunks; ++c) M = fmaxf(M, a.part_ml[((unit0 + c) * 32 + row) * 2]);
-    const int t = threadIdx.x;
-    if (t >= HD / 4) return;
+    for (int c = threadIdx.x; c < nchunks; c += 256) M = fmaxf(M, a.part_ml[((unit0 + c) * 32 + row) * 2]);
+    sh_m[threadIdx.x] = M;
+    __syncthreads();
+    for (int s2 = 128; s2 > 0; s2 >>= 1) {
+        if ((int)threadIdx.x < s2) sh_m[threadIdx.x] = fmaxf(sh_m[threadIdx.x], sh_m[threadIdx.x + s2]);
+        __syncthreads();
+    }
+    M = sh_m[0];
+    const int t = threadIdx.x % TPC, cg = threadIdx.x / TPC;
     float acc[4] = {0.f, 0.f, 0.f, 0.f}, L = 0.f;
-    for (int c = 0; c < nchunks; ++c) {
+    for (int c = cg; c < nchunks; c += NG) {
         const float *pm = a.part_ml + ((unit0 + c) * 32 + row) * 2;
         const float w = (pm[0] == -INFINITY) ? 0.f : expf(pm[0] - M);
         L += pm[1] * w;
         const float4 o = *(const float4 *)(a.part_o + ((unit0 + c) * 32 + row) * HD + 4 * t);
         acc[0] += w * o.x; acc[1] += w * o.y; acc[2] += w * o.z; acc[3] += w * o.w;
+    }
+    sh_acc[cg][t][0] = acc[0]; sh_acc[cg][t][1] = acc[1]; sh_acc[cg][t][2] = acc[2]; sh_acc[cg][t][3] = acc[3]; sh_acc[cg][t][4] = L;
+    __syncthreads();
+    if (cg != 0) return;
+    for (int o2 = 1; o2 < NG; ++o2) {
+        acc[0] += sh_acc[o2][t][0]; acc[1] += sh_acc[o2][t][1]; acc[2] += sh_acc[o2][t][2]; acc[3] += sh_acc[o2][t][3]; L += sh_acc[o2][t][4];
     }
     const float inv = 1.0f / L;
     const float y[4] = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
@@ -243,10 +249,10 @@ static int launch(pv_cache *c, attn_args &a, int rows, hipStream_t s)
     const pv_model_config &f = c->m->cfg;
     const int nrows = a.group * rows, mp = (nrows + 31) / 32;
     const dim3 grid(a.max_chunks, f.n_kv_heads, mp);
-    if (nrows <= 16) k_attn<HD, 1><<<grid, 256, 0, s>>>(a);
-    else k_attn<HD, 2><<<grid, 256, 0, s>>>(a);
+    if (nrows <= 16) k_attn<HD, 1><<<grid, 512, 0, s>>>(a);
+    else k_attn<HD, 2><<<grid, 512, 0, s>>>(a);
     PV_HIP(hipGetLastError());
-    k_attn_merge<NB, HD><<<dim3(rows, f.n_q_heads), 64, 0, s>>>(a, mp);
+    k_attn_merge<NB, HD><<<dim3(rows, f.n_q_heads), 256, 0, s>>>(a, mp);
     PV_HIP(hipGetLastError());
     return PV_OK;
 }

@@ -29,3 +29,20 @@ def logit_scale(ref_logits):
 def top2_margin(ref_logits):
     s = np.sort(np.asarray(ref_logits), axis=-1)
     return s[..., -1] - s[..., -2]
+
+
+def paired_models(shape, max_gamma=16, real="f64"):
+    """(library model, oracle model) built from the same generated tensors, each tensor drawn once.
+    The oracle borrows the host arrays; the library gets them chunk by chunk."""
+    from oracle import ref
+    gm = pv.Model(shape, max_gamma=max_gamma)
+    rm = ref.RefModel(shape, real=real)
+    for kind, layer in pv_inputs.iter_tensors(shape):
+        tshape = pv_inputs.tensor_shape(shape, kind)
+        arr = pv_inputs.fill_tensor(shape, kind, layer).reshape(tshape)
+        rm.set_tensor(kind, layer, arr)
+        a2 = arr.reshape(-1, tshape[-1])
+        step = gm.chunk_rows(tshape[-1])
+        for r0 in range(0, a2.shape[0], step):
+            gm.load_weights(kind, layer, r0, a2[r0:r0 + step])
+    return gm, rm

@@ -1,0 +1,132 @@
+"""Parity at the benchmark shapes (bf16, matrix-core path), in the launch configuration bench.py times.
+
+The oracle cannot prefill a 2048-token prompt through 32 full-width layers in test time, so each
+shape is covered by two element-by-element comparisons that together span every dimension at
+full size - (a) every layer at full width on a short prompt, (b) the full prompt length and
+every gamma on the first two layers - plus properties that hold at any size on the complete
+configuration (block forward == single-token steps, bit-exact rollback, lossless acceptance
+against the library's own greedy decoding).
+Bars: |dlogit| <= 3e-2 x RMS(logits of the row) (stated for bf16 storage; the split-bf16
+activations are expected near 1e-3, asserted at 5e-3); argmax / accepted_len / next_token
+bit-exact wherever the oracle's top-2 margin exceeds 0.05.
+"""
+import time
+
+import numpy as np
+import pytest
+
+import pv_inputs
+from pv_inputs import CONFIGS
+from oracle import ref
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pvlib():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2505_01572_amd as pv
+    return pv
+
+
+def _compare_steps(pvlib, gm, rm, shape, T0, gammas, alpha, seed, expect=5e-3):
+    from gpu_helpers import logit_scale, top2_margin
+    prompt = pv_inputs.uniform_tokens(2000 + shape.seed, T0, shape.vocab)
+    span = sum(gammas) + 8
+    gc, rc = pvlib.Cache(gm, T0 + span), ref.RefCache(rm, T0 + span, ref.KV_BF16)
+    t0 = time.time(); gc.prefill(prompt); t1 = time.time(); rc.prefill(prompt); t2 = time.time()
+    print(f"[{shape.name} L={shape.n_layers} T={T0}] prefill gpu {t1 - t0:.2f}s oracle {t2 - t1:.2f}s", flush=True)
+    assert gc.state()[0] == T0
+    worst = 0.0
+    for step, gamma in enumerate(gammas):
+        T = len(rc)
+        # draft: the oracle's own greedy tokens (teacher: previous preds), perturbed at rate 1-alpha
+        d = pv_inputs.uniform_tokens(seed + step, gamma, shape.vocab)
+        d[0] = rc.pending
+        n_r, t_r, pred_r, lg_r = rc.verify(T, d, want_logits=True)
+        # second pass with a draft that follows the oracle's predictions, perturbed: exercises accepts
+        rc.rollback(T); rc.pending = int(d[0])
+        d2 = np.concatenate([[d[0]], pred_r[:-1]]).astype(np.int32)
+        d2 = pv_inputs.perturb_drafts(d2, alpha, shape.vocab, seed, step); d2[0] = d[0]
+        n_r, t_r, pred_r, lg_r = rc.verify(T, d2, want_logits=True)
+        if gc.pending != d2[0]:
+            gc.set_pending(int(d2[0]))
+        n_g, t_g = gc.verify(T, d2)
+        lg_g = gc.debug_logits()
+        err = (np.abs(lg_g - lg_r) / logit_scale(lg_r)).max()
+        worst = max(worst, err)
+        assert err < 3e-2, f"gamma {gamma}: rel logit error {err}"
+        safe = top2_margin(lg_r) > 0.05
+        assert np.array_equal(gc.debug_pred()[safe], pred_r[safe])
+        if safe[: max(n_r, 1)].all():
+            assert (n_g, t_g) == (n_r, t_r), f"gamma {gamma}"
+            assert gc.state() == (len(rc), rc.pending)
+        else:
+            gc.rollback(T); rc.rollback(T)
+            gc.set_pending(int(d2[0])); rc.pending = int(d2[0])
+        print(f"  gamma {gamma}: accepted {n_r}, rel err {err:.2e}, safe rows {int(safe.sum())}/{gamma}", flush=True)
+    assert worst < expect, worst
+    return gc, rc
+
+
+@pytest.mark.parametrize("name,T0", [("8b", 2048), ("7b", 512), ("70b", 1024), ("1b", 1024)])
+def test_full_prefix_two_layers(pvlib, name, T0):
+    """Full width, full prompt length, gamma in {1,4,8,16}; first two layers (+ final norm and LM head)."""
+    from gpu_helpers import paired_models
+    shape = CONFIGS[name].replace(n_layers=2)
+    gm, rm = paired_models(shape)
+    gc, rc = _compare_steps(pvlib, gm, rm, shape, T0, (1, 4, 8, 16), 0.7, 7000)
+    ge = pv_inputs.bf16_bits_to_f32(gc.export()).astype(np.float64)
+    re_ = rc.export()
+    assert ge.shape == re_.shape and np.mean(ge != re_) < 0.05
+    assert np.abs(ge - re_).max() <= 2.0 ** -7 * np.abs(re_).max()
+
+
+@pytest.mark.parametrize("name,T0", [("8b", 96), ("7b", 96)])
+def test_full_depth_short_prefix(pvlib, name, T0):
+    """Every layer at full width; the prompt is cut to what the oracle prefills in seconds."""
+    from gpu_helpers import paired_models
+    shape = CONFIGS[name]
+    t0 = time.time()
+    gm, rm = paired_models(shape)
+    print(f"[{name}] models built in {time.time() - t0:.1f}s", flush=True)
+    # 1-ulp differences in which way a stored bf16 K/V element rounded (about 1 % of them, see the
+    # two-layer test) compound over 32 layers; the stated bar of 3e-2 still holds with margin
+    _compare_steps(pvlib, gm, rm, shape, T0, (8, 8), 0.7, 7100, expect=2e-2)
+
+
+def test_8b_full_configuration_properties(pvlib):
+    """Config 3 as benchmarked (32 layers, prefix 2048, paged KV): properties that need no oracle."""
+    import bench
+    shape = CONFIGS["8b"]
+    gm = bench.load_model(pvlib, pv_inputs, shape, 16)
+    T0, gamma = 2048, 8
+    c = pvlib.Cache(gm, T0 + 96)
+    c.prefill(pv_inputs.uniform_tokens(2000 + shape.seed, T0, shape.vocab))
+    first = c.pending
+    # greedy continuation by single-token steps, keeping each step's logits
+    G, seq_logits = [first], []
+    for i in range(gamma):
+        n, nxt = c.verify(T0 + i, [G[-1]]); assert n == 1
+        seq_logits.append(c.debug_logits()[0]); G.append(nxt)
+    c.rollback(T0)
+    before = c.export()
+    c.set_pending(first)
+    # block forward of the greedy tokens == the single-token steps; everything accepted
+    n, nxt = c.verify(T0, G[:gamma])
+    blk = c.debug_logits()
+    scale = np.sqrt((blk ** 2).mean())
+    assert np.abs(blk - np.stack(seq_logits)).max() < 2e-3 * scale
+    assert (n, nxt) == (gamma, G[gamma])
+    # a perturbed draft is cut at the first mismatch and corrected with the greedy token
+    c.rollback(T0); c.set_pending(first)
+    d = np.array(G[:gamma], dtype=np.int32); d[3] = (d[3] + 1) % shape.vocab
+    assert c.verify(T0, d) == (3, G[3])
+    assert c.state() == (T0 + 3, G[3])
+    # rollback restores the cache bit for bit and reruns are bit-identical
+    c.rollback(T0)
+    assert np.array_equal(c.export(), before)
+    c.set_pending(first)
+    assert c.verify(T0, G[:gamma]) == (gamma, G[gamma])
+    assert np.array_equal(c.debug_logits(), blk)
