@@ -1,0 +1,181 @@
+// Fused epilogues of the streaming GEMMs, shared by the per-GEMM kernels and the fused step
+// kernel.  An epilogue runs in one wavefront that holds the complete 16-feature x 16-column
+// accumulator of a strip: lane l has features 4*(l/16)+r (r = 0..3) of column l%16.
+#pragma once
+#include "pv_matrix_common.h"
+
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
+
+struct gemm_args {
+    const uint4 *W;             // tiled region, strip-major
+    const uint4 *xop;           // operand (hi [+ lo array behind it when NB == 2])
+    int ktiles;                 // K / 32
+    const pv_dev_state *st;
+    // RMSNorm scale of the input rows (QKV, SWIGLU, LMHEAD)
+    const float *ssq; int ssq_parts; float inv_d, eps;
+    // QKV
+    float *q; uint16_t *pool; const int32_t *page_table; const float2 *rope; pv_kv_geom geom;
+    int layer, n_q_heads, q_strips, k_strips;
+    // RESID
+    float *x; const uint16_t *gain_next; float *ssq_out; uint16_t *xop_out; int d;
+    // SWIGLU
+    uint16_t *xop_act; int F;
+    // LMHEAD
+    float *logits; float *pmax_val; int32_t *pmax_idx; int vocab;
+};
+
+// Shared tail of everything that produces a new residual stream value: store x, the partial
+// sum of squares of this 16-feature strip, and (gain * x) as the next GEMM's operand.
+template <int NB>
+__device__ inline void emit_x(int lane, int rows, int strip, int d, const float v[4], uint2 gain4,
+                              float *x, float *ssq, uint16_t *xop)
+{
+    const int j = lane & 15, g = lane >> 4, n = strip * 16 + 4 * g;
+    const bool live = j < rows;
+    if (live) *(float4 *)(x + (size_t)j * d + n) = make_float4(v[0], v[1], v[2], v[3]);
+    float ss = live ? (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]) : 0.f;
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (lane < 16) ssq[strip * 16 + j] = ss;
+    if (live) {
+        const float y[4] = {v[0] * pv_bf16_to_f32((uint16_t)(gain4.x & 0xffffu)), v[1] * pv_bf16_to_f32((uint16_t)(gain4.x >> 16)),
+                            v[2] * pv_bf16_to_f32((uint16_t)(gain4.y & 0xffffu)), v[3] * pv_bf16_to_f32((uint16_t)(gain4.y >> 16))};
+        store_operand4<NB>(xop, d, j, n, y);
+    }
+}
+
+// rsqrt(mean(x_j^2) + eps) for row j = lane % 16 from the [parts][16] partial sums, summed in a
+// fixed order.  All loads are independent (a serial chain of L2 round trips would cost far more
+// than the weight stream it sits beside): lane l reads float4 number l, l+64, ... so it always
+// sees rows 4*(l%4)..+3; lanes with equal l%4 are then combined and the result redistributed.
+__device__ inline float row_rscale(const float *ssq, int parts, float inv_d, float eps, int lane)
+{
+    const float4 *q = (const float4 *)ssq;
+    const int n4 = parts * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i0 = lane; i0 < n4; i0 += 64 * 8) {
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { const int i = i0 + u * 64; v[u] = i < n4 ? q[i] : make_float4(0.f, 0.f, 0.f, 0.f); }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+    }
+#pragma unroll
+    for (int o = 4; o <= 32; o <<= 1) {
+        s.x += __shfl_xor(s.x, o, 64); s.y += __shfl_xor(s.y, o, 64); s.z += __shfl_xor(s.z, o, 64); s.w += __shfl_xor(s.w, o, 64);
+    }
+    const int j = lane & 15, src = j >> 2;
+    const float t0 = __shfl(s.x, src, 64), t1 = __shfl(s.y, src, 64), t2 = __shfl(s.z, src, 64), t3 = __shfl(s.w, src, 64);
+    const float tot = (j & 3) == 0 ? t0 : (j & 3) == 1 ? t1 : (j & 3) == 2 ? t2 : t3;
+    return 1.0f / sqrtf(tot * inv_d + eps);
+}
+
+// What an epilogue needs from memory.  The owner wave fetches it before it starts streaming so
+// that after the reduction only arithmetic and stores remain.
+struct epi_pre {
+    float rj;
+    int rows, pos, phys;
+    float4 xo;
+    uint2 gn;
+    float2 cs[4];
+};
+
+template <int EPI>
+__device__ inline void epi_prefetch(const gemm_args &a, int strip, int lane, epi_pre &p)
+{
+    constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
+    const int j = lane & 15, g = lane >> 4;
+    p.rj = 1.f; p.pos = 0; p.phys = 0;
+    p.xo = make_float4(0.f, 0.f, 0.f, 0.f); p.gn = make_uint2(0u, 0u);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) p.cs[r] = make_float2(1.f, 0.f);
+    p.rows = a.st->gamma;
+    if (NORM) p.rj = row_rscale(a.ssq, a.ssq_parts, a.inv_d, a.eps, lane);
+    if (EPI == EPI_RESID) {
+        const int n = strip * 16 + 4 * g;
+        if (j < p.rows) p.xo = *(const float4 *)(a.x + (size_t)j * a.d + n);
+        p.gn = *(const uint2 *)(a.gain_next + n);
+    }
+    if (EPI == EPI_QKV) {
+        p.pos = a.st->len + j;
+        if (j < p.rows) {
+            if (strip >= a.q_strips) p.phys = a.page_table[p.pos >> a.geom.page_shift];
+            if (strip < a.q_strips + a.k_strips) {
+                const int spH = a.geom.head_dim >> 4, tt = strip % spH, e = tt * 8 + 4 * (g & 1);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) p.cs[r] = a.rope[(size_t)j * (a.geom.head_dim >> 1) + e + r];
+            }
+        }
+    }
+}
+
+// sum = the strip's accumulator (already summed over the K split)
+template <int NB, int EPI>
+__device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 sum, const epi_pre &p)
+{
+    constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
+    const int j = lane & 15, g = lane >> 4, rows = p.rows;
+    float v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) v[r] = (NB == 1) ? sum[r] + __shfl_down(sum[r], 8, 64) : sum[r];
+    const bool live = j < rows;          // NB == 1 implies rows <= 8, so live lanes hold the combined value
+    if (NORM) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] *= p.rj;
+    }
+
+    if (EPI == EPI_QKV) {
+        const pv_kv_geom &gm = a.geom;
+        const int hd = gm.head_dim, half = hd >> 1, spH = hd >> 4;
+        const int tok = p.pos & (gm.page_tokens - 1);
+        if (strip < a.q_strips + a.k_strips) {
+            const int h = strip / spH, tt = strip - h * spH, side = g >> 1, e = tt * 8 + 4 * (g & 1);
+            float o[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float partner = __shfl_xor(v[r], 32, 64);
+                o[r] = side ? v[r] * p.cs[r].x + partner * p.cs[r].y : v[r] * p.cs[r].x - partner * p.cs[r].y;
+            }
+            if (live) {
+                if (strip < a.q_strips) {
+                    *(float4 *)(a.q + ((size_t)j * a.n_q_heads + h) * hd + e + side * half) = make_float4(o[0], o[1], o[2], o[3]);
+                } else {
+                    const int kvh = h - a.n_q_heads;
+                    uint16_t *kp = a.pool + pv_kv_block(gm, a.layer, p.phys, kvh, 0) + pv_k_off(gm, tok, e + side * half);
+                    *(uint2 *)kp = make_uint2(bf16_rne(o[0]) | ((uint32_t)bf16_rne(o[1]) << 16), bf16_rne(o[2]) | ((uint32_t)bf16_rne(o[3]) << 16));
+                }
+            }
+        } else if (live) {
+            const int sv = strip - a.q_strips - a.k_strips, kvh = sv / spH, e = (sv - kvh * spH) * 16 + 4 * g;
+            uint16_t *vp = a.pool + pv_kv_block(gm, a.layer, p.phys, kvh, 1);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) vp[pv_v_off(gm, tok, e + r)] = bf16_rne(v[r]);
+        }
+    } else if (EPI == EPI_RESID) {
+        v[0] += p.xo.x; v[1] += p.xo.y; v[2] += p.xo.z; v[3] += p.xo.w;       // xo is zero on dead lanes
+        emit_x<NB>(lane, rows, strip, a.d, v, p.gn, a.x, a.ssq_out, a.xop_out);
+    } else if (EPI == EPI_SWIGLU) {
+        float act[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float up = __shfl_xor(v[r], 32, 64);
+            act[r] = v[r] / (1.0f + expf(-v[r])) * up;
+        }
+        if (live && g < 2) store_operand4<NB>(a.xop_act, a.F, j, strip * 8 + 4 * g, act);
+    } else {   // EPI_LMHEAD
+        const int n = strip * 16 + 4 * g;
+        if (live) *(float4 *)(a.logits + (size_t)j * a.vocab + n) = make_float4(v[0], v[1], v[2], v[3]);
+        float bv = -INFINITY; int bi = 0x7fffffff;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float val = (v[r] == v[r]) ? v[r] : -INFINITY;
+            if (val > bv || (val == bv && n + r < bi)) { bv = val; bi = n + r; }
+        }
+#pragma unroll
+        for (int o = 16; o <= 32; o <<= 1) {
+            const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if (lane < 16) { a.pmax_val[strip * 16 + j] = bv; a.pmax_idx[strip * 16 + j] = bi; }
+    }
+}
