@@ -37,9 +37,9 @@ def log(msg):
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
-def load_model(pv, pv_inputs, shape, max_gamma):
+def load_model(pv, pv_inputs, shape, max_gamma, kernel_path=0):
     t0 = time.time()
-    m = pv.Model(shape, max_gamma=max_gamma)
+    m = pv.Model(shape, max_gamma=max_gamma, kernel_path=kernel_path)
     done = 0
     total = shape.n_params()
     # one pinned host buffer, reused for every chunk (no fresh page faults, fast host-to-device copies)

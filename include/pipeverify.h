@@ -67,7 +67,7 @@ typedef enum {
 typedef enum {
     PV_PATH_AUTO = 0,    /* PV_F32 -> vector path, PV_BF16 -> matrix-core path            */
     PV_PATH_VECTOR = 1,  /* row-major weights, fp32 vector-ALU kernels (any storage type)  */
-    PV_PATH_MATRIX = 2   /* bf16 weights repacked into MFMA tiles, streamed through LDS    */
+    PV_PATH_MATRIX = 2   /* bf16 weights repacked into MFMA tiles, streamed by fused GEMMs */
 } pv_kernel_path;
 
 typedef struct {

@@ -50,14 +50,14 @@ static int check_config(const pv_model_config *c)
     if (c->head_dim % 2 || c->head_dim > 256) { pv_set_error("head_dim must be even and <= 256"); return PV_EINVAL; }
     if (c->dtype != PV_F32 && c->dtype != PV_BF16) { pv_set_error("bad dtype"); return PV_EINVAL; }
     if (!is_pow2(c->page_tokens)) { pv_set_error("page_tokens must be a power of two"); return PV_EINVAL; }
-    if (resolve_path(c) == PV_PATH_MATRIX && c->max_gamma > 16) { pv_set_error("matrix path: max_gamma must be <= 16"); return PV_EINVAL; }
+    if (resolve_path(c) >= PV_PATH_MATRIX && c->max_gamma > 16) { pv_set_error("matrix path: max_gamma must be <= 16"); return PV_EINVAL; }
     if (c->max_gamma < 1 || c->max_gamma > PV_MAX_ROWS) { pv_set_error("max_gamma must be in [1, %d]", PV_MAX_ROWS); return PV_EINVAL; }
     if (!(c->rms_eps > 0) || !(c->rope_base > 1)) { pv_set_error("bad rms_eps / rope_base"); return PV_EINVAL; }
     const int path = resolve_path(c);
     if (path != PV_PATH_VECTOR && path != PV_PATH_MATRIX) { pv_set_error("bad kernel_path"); return PV_EINVAL; }
     const int qd = c->n_q_heads * c->head_dim;
     if (c->d_model % 4 || c->ffn_dim % 4 || qd % 4) { pv_set_error("d_model, ffn_dim, q_dim must be multiples of 4"); return PV_EINVAL; }
-    if (path == PV_PATH_MATRIX) {
+    if (path >= PV_PATH_MATRIX) {
         if (c->dtype != PV_BF16) { pv_set_error("matrix path needs bf16 storage"); return PV_EINVAL; }
         if (c->d_model % 32 || c->ffn_dim % 32 || qd % 32 || c->vocab % 16 || (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) || c->page_tokens < 16) {
             pv_set_error("matrix path: d_model, ffn_dim, q_dim %% 32, vocab %% 16, head_dim in {32, 64, 128}, page_tokens >= 16 required");
@@ -102,7 +102,7 @@ static size_t layout_arena(const pv_model_config *c, pv_model *m)
         place(PV_T_FFN_NORM, l);
         const size_t gu = off;
         place(PV_T_WG, l); place(PV_T_WU, l);
-        if (m && path == PV_PATH_MATRIX) {                            // gate/up strips interleaved in one region
+        if (m && path >= PV_PATH_MATRIX) {                            // gate/up strips interleaved in one region
             pv_tensor_ref &g = m->layer[(size_t)l * PV_T_NKINDS + PV_T_WG], &u = m->layer[(size_t)l * PV_T_NKINDS + PV_T_WU];
             g.off = u.off = gu; g.strip_mul = u.strip_mul = 2; g.strip_add = 0; u.strip_add = 1;
         }
@@ -121,7 +121,7 @@ extern "C" int pv_model_bytes(const pv_model_config *cfg, size_t *weight_bytes, 
     if (rc != PV_OK) return rc;
     if (!weight_bytes || !staging_bytes) { pv_set_error("null output pointer"); return PV_EINVAL; }
     *weight_bytes = layout_arena(cfg, nullptr);
-    *staging_bytes = resolve_path(cfg) == PV_PATH_MATRIX ? STAGING_BYTES : 256;
+    *staging_bytes = resolve_path(cfg) >= PV_PATH_MATRIX ? STAGING_BYTES : 256;
     return PV_OK;
 }
 
@@ -178,7 +178,7 @@ extern "C" int pv_load_weights(pv_model *m, int32_t kind, int32_t layer, int64_t
     if (row_begin < 0 || row_count <= 0 || row_begin + row_count > t.rows) { pv_set_error("rows [%lld, +%lld) outside tensor of %lld rows", (long long)row_begin, (long long)row_count, (long long)t.rows); return PV_ERANGE; }
     hipStream_t s = (hipStream_t)hip_stream;
     const size_t nbytes = (size_t)row_count * t.cols * m->elt;
-    const bool tiled = m->path == PV_PATH_MATRIX && t.rows > 1 && kind != PV_T_EMBED;
+    const bool tiled = m->path >= PV_PATH_MATRIX && t.rows > 1 && kind != PV_T_EMBED;
     if (!tiled) {
         PV_HIP(hipMemcpyAsync(m->d_weights + t.off + (size_t)row_begin * t.cols * m->elt, host_rows, nbytes, hipMemcpyHostToDevice, s));
         PV_HIP(hipStreamSynchronize(s));
@@ -227,7 +227,7 @@ static size_t layout_ws(const pv_model *m, int rows_cap, int n_pages, pv_ws *w, 
     p = take(4 * R * c.ffn_dim); if (w) w->gate = (float *)p;
     p = take(4 * R * c.ffn_dim); if (w) w->up = (float *)p;
     p = take(4 * R * (size_t)c.vocab); if (w) w->logits = (float *)p;
-    const size_t pf = m->path == PV_PATH_MATRIX ? pv_mat_part_floats(m, rows_cap, n_pages * m->cfg.page_tokens) : 0;
+    const size_t pf = m->path >= PV_PATH_MATRIX ? pv_mat_part_floats(m, rows_cap, n_pages * m->cfg.page_tokens) : 0;
     p = take(4 * pf + 256); if (w) { w->part = (float *)p; w->part_floats = pf; }
     return off;
 }
@@ -323,7 +323,7 @@ static int enqueue_block(pv_cache *c, const int32_t *tokens, int rows, int mode,
     PV_HIP(hipMemcpyAsync(c->ws.state->draft, c->io->draft, sizeof(int32_t) * rows, hipMemcpyHostToDevice, s));
     int rc = pv_k_set_step(c, rows, mode, s);
     if (rc != PV_OK) return rc;
-    rc = m->path == PV_PATH_MATRIX ? pv_mat_run_block(c, s) : pv_vec_run_block(c, s);
+    rc = m->path >= PV_PATH_MATRIX ? pv_mat_run_block(c, s) : pv_vec_run_block(c, s);
     if (rc != PV_OK) return rc;
     // accepted, next_token -> mailbox; len/pending follow from them on the host
     PV_HIP(hipMemcpyAsync(c->io->result, &c->ws.state->accepted, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
@@ -416,7 +416,7 @@ extern "C" int pv_prefill(pv_cache *c, const int32_t *tokens, int32_t n, void *h
         rc = enqueue_block(c, tokens + off, rows, last ? PV_MODE_PREFILL_LAST : PV_MODE_PREFILL_MID, s);
         if (rc != PV_OK) return rc;
         PV_HIP(hipStreamSynchronize(s));          // the mailbox is reused by the next chunk
-        absorb_result(c);
+            absorb_result(c);
     }
     return PV_OK;
 }

@@ -59,7 +59,7 @@ struct pv_ws {                  // pointers into the caller's workspace
     int32_t *page_table;
     float2 *rope;               // [rows][head_dim/2] (cos, sin)
     float *x, *h, *q, *k, *v, *attn, *gate, *up, *logits;
-    float *part;                // matrix path: split-K partial sums
+    float *part;                // matrix path: operands, partial sums, attention partials
     size_t part_floats;
 };
 

@@ -161,7 +161,7 @@ pv_kv_geom pv_geom(const pv_cache *c)
     pv_kv_geom g;
     g.n_pages = c->n_pages; g.n_kv_heads = c->m->cfg.n_kv_heads; g.page_tokens = c->m->cfg.page_tokens;
     g.head_dim = c->m->cfg.head_dim;
-    g.tiled = c->m->path == PV_PATH_MATRIX;
+    g.tiled = c->m->path >= PV_PATH_MATRIX;
     g.page_shift = 0;
     while ((1 << g.page_shift) < g.page_tokens) ++g.page_shift;
     return g;

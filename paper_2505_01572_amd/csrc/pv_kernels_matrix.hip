@@ -211,7 +211,7 @@ k_argmax_parts(pv_dev_state *st, const float *pv, const int32_t *pi, int strips)
 
 // Waves per workgroup (= K split): enough waves to fill the machine even when there are few
 // strips, but no more than the K tiles can feed.
-static int g_tune_nw[4] = {0, 0, 0, 0};     // per epilogue kind; 0 = heuristic
+static int g_tune_nw[4] = {0, 0, 0, 0};     // per epilogue kind; 0 = heuristic, else waves per workgroup
 
 template <int NB, int EPI>
 static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStream_t s)
@@ -298,7 +298,6 @@ static int run_block(pv_cache *c, hipStream_t s)
 
 int pv_mat_run_block(pv_cache *c, hipStream_t s)
 {
-    if (const char *t = getenv("PV_TUNE_NW")) sscanf(t, "%d,%d,%d,%d", &g_tune_nw[0], &g_tune_nw[1], &g_tune_nw[2], &g_tune_nw[3]);
     if (c->last_rows > 16) { pv_set_error("matrix path handles at most 16 rows per block"); return PV_ERANGE; }
     return c->last_rows <= 8 ? run_block<1>(c, s) : run_block<2>(c, s);
 }

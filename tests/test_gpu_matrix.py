@@ -17,6 +17,9 @@ pytestmark = pytest.mark.gpu
 MAT_A = pv_inputs.ModelShape("mat_a", 3, 128, 8, 2, 32, 352, 512, rope_base=500000.0, dtype="bf16", seed=5151)
 MAT_B = pv_inputs.ModelShape("mat_b", 2, 1024, 8, 2, 128, 4128, 2000, rope_base=500000.0, dtype="bf16", seed=5252)
 MAT_C = pv_inputs.ModelShape("mat_c", 2, 512, 8, 8, 64, 1376, 1008, dtype="bf16", seed=5353)   # MHA, hd 64
+# larger K (multiples of 256): 16-wave K split with several tiles per wave, long ragged down-projection slice
+FUSE_A = pv_inputs.ModelShape("fuse_a", 2, 512, 8, 2, 64, 1280, 1008, rope_base=500000.0, dtype="bf16", seed=5454)
+FUSE_B = pv_inputs.ModelShape("fuse_b", 2, 1024, 8, 2, 128, 8448, 2000, rope_base=500000.0, dtype="bf16", seed=5555)
 
 
 @pytest.fixture(scope="module")
@@ -32,10 +35,13 @@ def _rel_err(pvlib, lg_g, lg_r):
     return (np.abs(lg_g - lg_r) / logit_scale(lg_r)).max()
 
 
-@pytest.mark.parametrize("shape", [MAT_A, MAT_B, MAT_C], ids=lambda s: s.name)
-def test_matrix_path_matches_oracle(pvlib, shape):
+CASES = [(MAT_A, 0), (MAT_B, 0), (MAT_C, 0), (FUSE_A, 0), (FUSE_B, 2)]
+
+
+@pytest.mark.parametrize("shape,path", CASES, ids=lambda v: v.name if hasattr(v, "name") else f"path{v}")
+def test_matrix_path_matches_oracle(pvlib, shape, path):
     from gpu_helpers import gpu_model, top2_margin
-    gm = gpu_model(shape, gains="perturbed")
+    gm = gpu_model(shape, gains="perturbed", kernel_path=path)
     rm = ref_model(shape, gains="perturbed")
     prompt = pv_inputs.uniform_tokens(61, 37, shape.vocab)
     gc, rc = pvlib.Cache(gm, 96), ref.RefCache(rm, 96, ref.KV_BF16)
@@ -44,7 +50,7 @@ def test_matrix_path_matches_oracle(pvlib, shape):
     assert _rel_err(pvlib, gc.debug_logits()[-1:], last[None]) < 2e-3
     assert gc.state() == (37, rc.pending)
     worst = 0.0
-    for step, gamma in enumerate((8, 13, 1, 5, 16)):
+    for step, gamma in enumerate((8, 13, 1, 5, 16, 3)):
         T = len(rc)
         d = pv_inputs.uniform_tokens(62 + step, gamma, shape.vocab)
         d[0] = rc.pending
