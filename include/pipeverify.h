@@ -160,6 +160,18 @@ int pv_verify_wait(pv_cache *c, int32_t *accepted_len, int32_t *next_token);
  */
 int pv_rollback(pv_cache *c, int32_t new_len, void *hip_stream);
 
+/*
+ * Re-admit positions of the block the last pv_verify / pv_prefill call ran over: set the length
+ * to new_len, where (length after that call) <= new_len <= (prefix_len + gamma of that call), and
+ * pending to `pending` (-1 = unknown).  Metadata only: the K/V of those positions were written
+ * by that call and are still in place.  This exists for drivers that decide acceptance
+ * outside the library - the three-stage pipeline benchmark on independent random models draws
+ * synthetic acceptances while every stage still runs its real forward pass.  PV_ESTATE if no
+ * such block is on record (a rollback, export or set_page_table forgets it), PV_ERANGE if
+ * new_len is outside the range above.  Synchronises hip_stream.
+ */
+int pv_cache_readmit(pv_cache *c, int32_t new_len, int32_t pending, void *hip_stream);
+
 /* ---- state and parity hooks ---- */
 
 int pv_cache_len(const pv_cache *c, int32_t *len, int32_t *pending /* -1 = unknown */);

@@ -34,7 +34,7 @@ EXPORTS = [
     "pv_cache_create", "pv_cache_destroy", "pv_cache_set_page_table", "pv_prefill", "pv_verify",
     "pv_verify_async", "pv_verify_wait", "pv_rollback", "pv_cache_len", "pv_cache_set_pending",
     "pv_debug_logits", "pv_debug_pred", "pv_cache_export", "pv_step_bytes", "pv_strerror", "pv_last_error",
-    "pv_profile_select", "pv_profile_read",
+    "pv_profile_select", "pv_profile_read", "pv_cache_readmit",
 ]
 
 _lib = None
@@ -63,6 +63,7 @@ def lib():
         L.pv_verify_async.argtypes = [vp, i32, vp, i32, vp]
         L.pv_verify_wait.argtypes = [vp, P(i32), P(i32)]
         L.pv_rollback.argtypes = [vp, i32, vp]
+        L.pv_cache_readmit.argtypes = [vp, i32, i32, vp]
         L.pv_cache_len.argtypes = [vp, P(i32), P(i32)]
         L.pv_cache_set_pending.argtypes = [vp, i32, vp]
         L.pv_debug_logits.argtypes = [vp, vp, P(i32), vp]
@@ -187,6 +188,10 @@ class Cache:
     def rollback(self, new_len, stream=None):
         with self._dev():
             _check(self.L.pv_rollback(self.h, new_len, _stream_ptr(stream)), "pv_rollback")
+
+    def readmit(self, new_len, pending=-1, stream=None):
+        with self._dev():
+            _check(self.L.pv_cache_readmit(self.h, new_len, pending, _stream_ptr(stream)), "pv_cache_readmit")
 
     def set_pending(self, token, stream=None):
         with self._dev():

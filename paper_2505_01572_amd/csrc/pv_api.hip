@@ -261,7 +261,7 @@ extern "C" int pv_cache_create(const pv_model *m, void *d_page_pool, size_t page
     c->max_tokens = max_tokens; c->n_pages = (max_tokens + m->cfg.page_tokens - 1) / m->cfg.page_tokens;
     c->rows_cap = rows_cap_of(m);
     layout_ws(m, c->rows_cap, c->n_pages, &c->ws, c->d_ws);
-    c->len = 0; c->pending = -1; c->last_rows = 0; c->in_flight = false; c->flight_stream = nullptr; c->io = nullptr;
+    c->len = 0; c->pending = -1; c->last_rows = 0; c->blk_start = 0; c->blk_rows = 0; c->in_flight = false; c->flight_stream = nullptr; c->io = nullptr;
     c->prof_kind = PV_PROF_NONE; c->prof_pending = 0; c->prof_ev = nullptr; c->prof_ms = 0; c->prof_launches = 0;
     if (hipHostMalloc((void **)&c->io, sizeof(pv_host_io), hipHostMallocDefault) != hipSuccess) {
         pv_set_error("hipHostMalloc failed"); delete c; return PV_EHIP;
@@ -320,6 +320,7 @@ static int enqueue_block(pv_cache *c, const int32_t *tokens, int rows, int mode,
     memcpy(c->io->draft, tokens, sizeof(int32_t) * rows);
     c->io->hdr[2] = rows; c->io->hdr[3] = mode;
     c->last_rows = rows;
+    c->blk_start = c->len; c->blk_rows = rows;
     PV_HIP(hipMemcpyAsync(c->ws.state->draft, c->io->draft, sizeof(int32_t) * rows, hipMemcpyHostToDevice, s));
     int rc = pv_k_set_step(c, rows, mode, s);
     if (rc != PV_OK) return rc;
@@ -473,7 +474,22 @@ extern "C" int pv_rollback(pv_cache *c, int32_t new_len, void *hip_stream)
     int rc = pv_k_set_state(c, new_len, -1, s);
     if (rc != PV_OK) return rc;
     PV_HIP(hipStreamSynchronize(s));
-    c->len = new_len; c->pending = -1;
+    c->len = new_len; c->pending = -1; c->blk_rows = 0;
+    return PV_OK;
+}
+
+extern "C" int pv_cache_readmit(pv_cache *c, int32_t new_len, int32_t pending, void *hip_stream)
+{
+    if (!c) { pv_set_error("null cache"); return PV_EINVAL; }
+    if (c->in_flight) { pv_set_error("a verify is in flight on this cache"); return PV_ESTATE; }
+    if (c->blk_rows == 0) { pv_set_error("no block on record to re-admit from"); return PV_ESTATE; }
+    if (new_len < c->len || new_len > c->blk_start + c->blk_rows) { pv_set_error("new_len %d outside [%d, %d]", new_len, c->len, c->blk_start + c->blk_rows); return PV_ERANGE; }
+    if (pending < -1 || pending >= c->m->cfg.vocab) { pv_set_error("token %d out of range", pending); return PV_ERANGE; }
+    hipStream_t s = (hipStream_t)hip_stream;
+    int rc = pv_k_set_state(c, new_len, pending, s);
+    if (rc != PV_OK) return rc;
+    PV_HIP(hipStreamSynchronize(s));
+    c->len = new_len; c->pending = pending;
     return PV_OK;
 }
 
@@ -540,6 +556,7 @@ extern "C" int pv_cache_export(pv_cache *c, void *host_out, size_t nbytes, void 
         PV_HIP(hipStreamSynchronize(s));
     }
     c->last_rows = 0;           // the logits buffer no longer holds a block's logits
+    c->blk_rows = 0;
     return PV_OK;
 }
 

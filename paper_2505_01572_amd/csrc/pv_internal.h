@@ -71,6 +71,7 @@ struct pv_cache {
     pv_ws ws;
     pv_host_io *io;             // pinned
     int32_t len, pending, last_rows;
+    int32_t blk_start, blk_rows;   // positions the last block wrote K/V for (blk_rows = 0: none on record)
     bool in_flight; hipStream_t flight_stream;
     // instrumentation: one kernel kind bracketed by events, one pair per layer
     int32_t prof_kind, prof_pending;
