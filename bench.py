@@ -27,6 +27,15 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes one launch of the dominant kernel moves, from hardware counters: FETCH_SIZE and
+# WRITE_SIZE of two separate rocprofv3 --pmc runs of this script, each scaled by what the same
+# counter reads for the library's plain copy kernel (--calib-copy) of known size.  Summary and
+# commands: profiles/hbm_traffic_pmc_8b_70b.txt.  Keyed by (workload, gamma bucket, kernel).
+MEASURED_TRAFFIC = {
+    ("8b", "rows<=8", "gateup"): 236741265 + 171176,
+    ("70b", "rows<=8", "gateup"): 960968020 + 342352,
+}
+
 DEFAULTS = {  # workload -> (prefix, gamma, alpha)
     "tiny": (64, 4, 0.7), "7b": (512, 8, 0.8), "8b": (2048, 8, 0.7), "70b": (1024, 8, 0.6),
     "1b": (1024, 1, 0.7), "70b_v128k": (1024, 8, 0.6),
@@ -103,6 +112,9 @@ def main():
     ap.add_argument("--alpha", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prof-kernel", default="gateup")
+    ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
+                    help="also launch the library's plain copy kernel on this many MiB three times (the known "
+                         "quantity that hardware traffic counters read under rocprofv3 --pmc are scaled by)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -183,6 +195,16 @@ def main():
     k_ms = ms / max(launches, 1)
     k_gbps = kbytes / (k_ms * 1e-3) / 1e9 if launches else 0.0
 
+    if a.calib_copy > 0:
+        src = torch.full((a.calib_copy << 20,), 1, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            pv.calib_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    traffic = MEASURED_TRAFFIC.get((a.workload, "rows<=8" if gamma <= 8 else "rows<=16", a.prof_kernel))
+
     out = {
         "metric": "verify_tokens_per_s", "value": gamma * K / elapsed, "unit": "tok/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
@@ -195,7 +217,7 @@ def main():
         "mean_accepted_len": accepted / K,
         "step_bytes": step_bytes, "step_hbm_gbps": hbm_gbps, "step_hbm_frac": hbm_gbps / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": f"k_gemm<{a.prof_kernel}>", "achieved": k_gbps, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": k_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "unit": "GB/s", "frac": k_gbps / HBM_PEAK_GBPS, "traffic": traffic,
                      "bytes_per_launch": kbytes, "avg_launch_us": k_ms * 1e3, "launches": launches},
     }
     if not a.no_cpu_baseline:

@@ -204,6 +204,12 @@ int pv_profile_select(pv_cache *c, int32_t which);
  * streams (its weights; for attention the K/V of the current length).  Only between steps. */
 int pv_profile_read(pv_cache *c, double *total_ms, int64_t *launches, uint64_t *bytes_per_launch);
 
+/* Plain device-to-device copy kernel (k_calib_copy) of `nbytes` bytes, a multiple of 16, both
+ * pointers device memory aligned to 16 bytes and not overlapping.  It reads nbytes and writes
+ * nbytes of HBM and nothing else: the known quantity against which hardware traffic counters
+ * read under a profiler are scaled.  Asynchronous on `hip_stream`. */
+int pv_calib_copy(void *d_dst, const void *d_src, size_t nbytes, void *hip_stream);
+
 const char *pv_strerror(int status);
 const char *pv_last_error(void);
 

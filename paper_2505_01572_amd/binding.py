@@ -34,7 +34,7 @@ EXPORTS = [
     "pv_cache_create", "pv_cache_destroy", "pv_cache_set_page_table", "pv_prefill", "pv_verify",
     "pv_verify_async", "pv_verify_wait", "pv_rollback", "pv_cache_len", "pv_cache_set_pending",
     "pv_debug_logits", "pv_debug_pred", "pv_cache_export", "pv_step_bytes", "pv_strerror", "pv_last_error",
-    "pv_profile_select", "pv_profile_read", "pv_cache_readmit",
+    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy",
 ]
 
 _lib = None
@@ -72,6 +72,7 @@ def lib():
         L.pv_step_bytes.argtypes = [vp, i32, P(ctypes.c_uint64)]
         L.pv_profile_select.argtypes = [vp, i32]
         L.pv_profile_read.argtypes = [vp, P(ctypes.c_double), P(i64), P(ctypes.c_uint64)]
+        L.pv_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.pv_strerror.argtypes = [ctypes.c_int]; L.pv_strerror.restype = ctypes.c_char_p
         L.pv_last_error.argtypes = []; L.pv_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -92,6 +93,14 @@ def _stream_ptr(stream):
 
 def _dev_bytes(n, device):
     return torch.empty(max(int(n), 256), dtype=torch.uint8, device=device)
+
+
+def calib_copy(dst, src, stream=None):
+    """Plain copy kernel of known size between two device tensors (counter calibration)."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n and dst.is_cuda and src.is_cuda
+    _check(lib().pv_calib_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), n, _stream_ptr(stream)),
+           "pv_calib_copy")
 
 
 class Model:

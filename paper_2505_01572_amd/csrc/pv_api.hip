@@ -386,6 +386,24 @@ extern "C" int pv_profile_read(pv_cache *c, double *total_ms, int64_t *launches,
     return PV_OK;
 }
 
+__global__ void __launch_bounds__(256) k_calib_copy(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+extern "C" int pv_calib_copy(void *d_dst, const void *d_src, size_t nbytes, void *hip_stream)
+{
+    if (!d_dst || !d_src || (nbytes & 15) || (((uintptr_t)d_dst | (uintptr_t)d_src) & 15)) {
+        pv_set_error("pv_calib_copy: pointers and size must be multiples of 16 bytes"); return PV_EINVAL;
+    }
+    const size_t n = nbytes / 16;
+    if (n == 0) return PV_OK;
+    const unsigned grid = (unsigned)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+    k_calib_copy<<<grid, 256, 0, (hipStream_t)hip_stream>>>((uint4 *)d_dst, (const uint4 *)d_src, n);
+    PV_HIP(hipGetLastError());
+    return PV_OK;
+}
+
 static void absorb_result(pv_cache *c)
 {
     prof_collect(c);
