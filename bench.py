@@ -138,6 +138,8 @@ def main():
     model = load_model(pv, pv_inputs, shape, max_gamma=16)
     max_tokens = T0 + (2 * n_steps + 2) * gamma + 16
     cache = pv.Cache(model, max_tokens)
+    if os.environ.get("PV_BENCH_GRAPHS") == "0":     # comparison runs: plain launches instead of graph replay
+        cache.use_graphs(False)
     prompt = pv_inputs.uniform_tokens(2000 + shape.seed, T0, shape.vocab)
     t0 = time.time()
     cache.prefill(prompt)

@@ -190,6 +190,12 @@ int pv_cache_export(pv_cache *c, void *host_out, size_t nbytes, void *hip_stream
  * weight once + K/V of length+gamma positions once + the K/V written. */
 int pv_step_bytes(const pv_cache *c, int32_t gamma, uint64_t *bytes);
 
+/* A step's launch sequence depends only on (row count, mode); by default it is recorded once per
+ * such pair as a HIP graph (stream capture on a private stream, thread-local mode) and replayed
+ * on the caller's stream afterwards.  enable = 0 switches to plain launches, for comparison and
+ * for callers that capture the step into a graph of their own.  Results are identical. */
+int pv_cache_use_graphs(pv_cache *c, int32_t enable);
+
 /* ---- instrumentation ---- */
 
 typedef enum {

@@ -34,7 +34,7 @@ EXPORTS = [
     "pv_cache_create", "pv_cache_destroy", "pv_cache_set_page_table", "pv_prefill", "pv_verify",
     "pv_verify_async", "pv_verify_wait", "pv_rollback", "pv_cache_len", "pv_cache_set_pending",
     "pv_debug_logits", "pv_debug_pred", "pv_cache_export", "pv_step_bytes", "pv_strerror", "pv_last_error",
-    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy",
+    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_cache_use_graphs",
 ]
 
 _lib = None
@@ -73,6 +73,7 @@ def lib():
         L.pv_profile_select.argtypes = [vp, i32]
         L.pv_profile_read.argtypes = [vp, P(ctypes.c_double), P(i64), P(ctypes.c_uint64)]
         L.pv_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.pv_cache_use_graphs.argtypes = [vp, i32]
         L.pv_strerror.argtypes = [ctypes.c_int]; L.pv_strerror.restype = ctypes.c_char_p
         L.pv_last_error.argtypes = []; L.pv_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -251,6 +252,9 @@ class Cache:
 
     def profile_select(self, which):
         _check(self.L.pv_profile_select(self.h, which), "pv_profile_select")
+
+    def use_graphs(self, enable):
+        _check(self.L.pv_cache_use_graphs(self.h, 1 if enable else 0), "pv_cache_use_graphs")
 
     def profile_read(self):
         ms, n, b = ctypes.c_double(), ctypes.c_int64(), ctypes.c_uint64()

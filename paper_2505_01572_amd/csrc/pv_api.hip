@@ -263,6 +263,8 @@ extern "C" int pv_cache_create(const pv_model *m, void *d_page_pool, size_t page
     layout_ws(m, c->rows_cap, c->n_pages, &c->ws, c->d_ws);
     c->len = 0; c->pending = -1; c->last_rows = 0; c->blk_start = 0; c->blk_rows = 0; c->in_flight = false; c->flight_stream = nullptr; c->io = nullptr;
     c->prof_kind = PV_PROF_NONE; c->prof_pending = 0; c->prof_ev = nullptr; c->prof_ms = 0; c->prof_launches = 0;
+    c->use_graphs = true; c->cap_stream = nullptr;
+    for (auto &row : c->gexec) for (auto &ge : row) ge = nullptr;
     if (hipHostMalloc((void **)&c->io, sizeof(pv_host_io), hipHostMallocDefault) != hipSuccess) {
         pv_set_error("hipHostMalloc failed"); delete c; return PV_EHIP;
     }
@@ -286,6 +288,8 @@ extern "C" void pv_cache_destroy(pv_cache *c)
 {
     if (!c) return;
     if (c->io) (void)hipHostFree(c->io);
+    for (auto &row : c->gexec) for (auto &ge : row) if (ge) (void)hipGraphExecDestroy(ge);
+    if (c->cap_stream) (void)hipStreamDestroy(c->cap_stream);
     if (c->prof_ev) {
         for (int i = 0; i < 2 * c->m->cfg.n_layers; ++i) (void)hipEventDestroy(c->prof_ev[i]);
         free(c->prof_ev);
@@ -312,6 +316,20 @@ extern "C" int pv_cache_set_page_table(pv_cache *c, const int32_t *phys_pages, i
 
 // ---- the step ----
 
+// the step's launches on stream s: draft ids in, block forward, acceptance, two results out
+static int record_block(pv_cache *c, int rows, int mode, hipStream_t s)
+{
+    const pv_model *m = c->m;
+    PV_HIP(hipMemcpyAsync(c->ws.state->draft, c->io->draft, sizeof(int32_t) * rows, hipMemcpyHostToDevice, s));
+    int rc = pv_k_set_step(c, rows, mode, s);
+    if (rc != PV_OK) return rc;
+    rc = m->path >= PV_PATH_MATRIX ? pv_mat_run_block(c, s) : pv_vec_run_block(c, s);
+    if (rc != PV_OK) return rc;
+    // accepted, next_token -> mailbox; len/pending follow from them on the host
+    PV_HIP(hipMemcpyAsync(c->io->result, &c->ws.state->accepted, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    return PV_OK;
+}
+
 static int enqueue_block(pv_cache *c, const int32_t *tokens, int rows, int mode, hipStream_t s)
 {
     const pv_model *m = c->m;
@@ -321,14 +339,27 @@ static int enqueue_block(pv_cache *c, const int32_t *tokens, int rows, int mode,
     c->io->hdr[2] = rows; c->io->hdr[3] = mode;
     c->last_rows = rows;
     c->blk_start = c->len; c->blk_rows = rows;
-    PV_HIP(hipMemcpyAsync(c->ws.state->draft, c->io->draft, sizeof(int32_t) * rows, hipMemcpyHostToDevice, s));
-    int rc = pv_k_set_step(c, rows, mode, s);
-    if (rc != PV_OK) return rc;
-    rc = m->path >= PV_PATH_MATRIX ? pv_mat_run_block(c, s) : pv_vec_run_block(c, s);
-    if (rc != PV_OK) return rc;
-    // accepted, next_token -> mailbox; len/pending follow from them on the host
-    PV_HIP(hipMemcpyAsync(c->io->result, &c->ws.state->accepted, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    return PV_OK;
+    // The launch sequence depends on (rows, mode) only: everything else a kernel needs (length,
+    // pending token, draft ids) it reads from device memory.  So the sequence is recorded once
+    // per (rows, mode) as a HIP graph and replayed; instrumented steps run the plain launches.
+    if (c->use_graphs && c->prof_kind == PV_PROF_NONE) {
+        hipGraphExec_t &ge = c->gexec[rows][mode];
+        if (!ge) {
+            if (!c->cap_stream) PV_HIP(hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking));
+            PV_HIP(hipStreamBeginCapture(c->cap_stream, hipStreamCaptureModeThreadLocal));
+            const int rrc = record_block(c, rows, mode, c->cap_stream);
+            hipGraph_t g = nullptr;
+            const hipError_t e = hipStreamEndCapture(c->cap_stream, &g);
+            if (rrc != PV_OK) { if (g) (void)hipGraphDestroy(g); return rrc; }
+            if (e != hipSuccess || !g) { pv_set_error("stream capture of the step failed: %s", hipGetErrorString(e)); return PV_EHIP; }
+            const hipError_t ei = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(g);
+            if (ei != hipSuccess) { ge = nullptr; pv_set_error("hipGraphInstantiate failed: %s", hipGetErrorString(ei)); return PV_EHIP; }
+        }
+        PV_HIP(hipGraphLaunch(ge, s));
+        return PV_OK;
+    }
+    return record_block(c, rows, mode, s);
 }
 
 int pv_prof_mark(pv_cache *c, int kind, int slot, int end, hipStream_t s)
@@ -347,6 +378,14 @@ static void prof_collect(pv_cache *c)
         if (hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]) == hipSuccess) { c->prof_ms += ms; c->prof_launches += 1; }
     }
     c->prof_pending = 0;
+}
+
+extern "C" int pv_cache_use_graphs(pv_cache *c, int32_t enable)
+{
+    if (!c) { pv_set_error("null cache"); return PV_EINVAL; }
+    if (c->in_flight) { pv_set_error("a verify is in flight on this cache"); return PV_ESTATE; }
+    c->use_graphs = enable != 0;
+    return PV_OK;
 }
 
 extern "C" int pv_profile_select(pv_cache *c, int32_t which)

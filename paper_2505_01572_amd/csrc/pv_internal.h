@@ -77,6 +77,10 @@ struct pv_cache {
     int32_t prof_kind, prof_pending;
     hipEvent_t *prof_ev;        // [2 * n_layers], created on first use
     double prof_ms; int64_t prof_launches;
+    // one instantiated HIP graph per (rows, mode) of the step's launch sequence, captured on first use
+    bool use_graphs;
+    hipStream_t cap_stream;     // private stream that only ever records
+    hipGraphExec_t gexec[PV_MAX_ROWS + 1][3];
 };
 
 // bracket helper used by the kernel families: records the start/end event of slot `slot`

@@ -125,3 +125,37 @@ def test_matrix_block_equals_sequential(pvlib):
         seq.append(b.debug_logits()[0])
     scale = np.sqrt((blk ** 2).mean())
     assert np.abs(blk - np.stack(seq)).max() < 1e-3 * scale
+
+
+def test_graph_replay_equals_plain_launches(pvlib):
+    """The step recorded as a HIP graph must give, on every replay, exactly what the plain launch
+    sequence gives: same accepted length, next token, predictions, logits bit for bit and the
+    same K/V.  Each row count is replayed several times, with unrelated eager GPU work and
+    synchronisations between the replays; both matrix (bf16) and vector (fp32) paths."""
+    import torch
+    from gpu_helpers import gpu_model
+    tiny = pv_inputs.CONFIGS["tiny"]
+    for shape in (FUSE_A, tiny):
+        gm = gpu_model(shape, gains="perturbed")
+        cg, cp = pvlib.Cache(gm, 256), pvlib.Cache(gm, 256)
+        cp.use_graphs(False)
+        prompt = pv_inputs.uniform_tokens(71, 41, shape.vocab)
+        cg.prefill(prompt); cp.prefill(prompt)          # 16-row chunks: the prefill graphs replay too
+        assert cg.state() == cp.state()
+        junk = torch.zeros(1 << 20, device="cuda")
+        for step, gamma in enumerate((8, 8, 3, 8, 16, 3, 1, 16, 8, 1, 3, 8)):
+            T, pending = cp.state()
+            d = pv_inputs.uniform_tokens(720 + step, gamma, shape.vocab)
+            if step % 3 != 2 and pending >= 0:
+                d[0] = pending
+            r_p = cp.verify(T, d)
+            junk.add_(1.0); s = float(junk.sum().item())   # eager kernels (a multi-block reduction among them) + sync
+            assert s == (step + 1) * junk.numel()
+            r_g = cg.verify(T, d)
+            assert r_g == r_p, (shape.name, step, gamma)
+            assert np.array_equal(cg.debug_pred(), cp.debug_pred())
+            assert np.array_equal(cg.debug_logits(), cp.debug_logits()), (shape.name, step, gamma)
+            assert cg.state() == cp.state()
+            if step == 5:                                  # an external rollback between replays
+                cg.rollback(T); cp.rollback(T)
+        assert np.array_equal(cg.export(), cp.export())
