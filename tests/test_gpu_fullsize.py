@@ -96,12 +96,18 @@ def test_full_depth_short_prefix(pvlib, name, T0):
     _compare_steps(pvlib, gm, rm, shape, T0, (8, 8), 0.7, 7100, expect=2e-2)
 
 
-def test_8b_full_configuration_properties(pvlib):
-    """Config 3 as benchmarked (32 layers, prefix 2048, paged KV): properties that need no oracle."""
+@pytest.mark.parametrize("name,T0", [("8b", 2048), ("70b", 1024)])
+def test_full_configuration_properties(pvlib, name, T0):
+    """Configs 3 and 4 as benchmarked (every layer, full prefix, paged KV, the launch configuration
+    bench.py times): properties that need no oracle."""
     import bench
-    shape = CONFIGS["8b"]
+    import gc
+    import torch
+    gc.collect(); torch.cuda.empty_cache()          # the 70B shape needs 140 GB of the card
+    shape = CONFIGS[name]
+    print(f"full configuration {name}: loading", flush=True)
     gm = bench.load_model(pvlib, pv_inputs, shape, 16)
-    T0, gamma = 2048, 8
+    gamma = 8
     c = pvlib.Cache(gm, T0 + 96)
     c.prefill(pv_inputs.uniform_tokens(2000 + shape.seed, T0, shape.vocab))
     first = c.pending
