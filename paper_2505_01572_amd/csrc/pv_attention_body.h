@@ -1,11 +1,14 @@
 // Causal grouped-query attention over the paged bf16 KV cache on the matrix cores.
 //
-// Work unit: one workgroup = (kv head, chunk of 256 keys, group of <= 32 query rows).  The
-// query rows of a kv head are its `group` query heads x gamma block rows, packed densely
-// (row m = head_in_group * gamma + j).  Each of the 8 wavefronts takes 32 keys; the eight
-// partial results are merged through LDS in a fixed order and written as one partial (max,
-// sum, output) per chunk; a small merge kernel combines the chunks and writes the attention
-// output directly as the output projection's split-bf16 operand.
+// Work unit: one workgroup of 8 wavefronts = (kv head, chunk of keys, group of <= 32 query
+// rows).  The query rows of a kv head are its `group` query heads x gamma block rows, packed
+// densely (row m = head_in_group * gamma + j).  Two shapes of the unit:
+//   TILES = 1: up to 16 rows, 256 keys; every wave takes 32 keys of the one 16-row tile;
+//   TILES = 2: 17..32 rows, 128 keys; wave w takes row tile w / 4 and 32 keys (w % 4).
+// Either way a wave makes one pass.  The waves of a row tile are merged through LDS (every
+// wave writes its rescaled partial, then all threads add them in wave order) into one partial
+// (max, sum, output) per chunk; a small merge kernel combines the chunks and writes the
+// attention output directly as the output projection's split-bf16 operand.
 //
 // Everything is computed transposed so that no register shuffling is needed:
 //   S^T (keys x rows) = K (keys x hd) * Q^T (hd x rows)      A = K tile, B = Q^T
@@ -18,6 +21,9 @@
 // of row lane%16 then sit in the same lane as that row's output accumulators.
 //
 // Q and P are carried as bf16 hi + lo pairs (two MFMAs each), K and V are the stored bf16.
+// Softmax weights use the hardware exponential (__expf, relative error ~1e-6 at these
+// arguments): they are rounded to 16 mantissa bits for the second product anyway.
+// Q arrives already split (the QKV projection's epilogue writes the two bf16 arrays).
 // The causal part only touches keys >= len: key p is visible to block row j iff p <= len + j.
 #pragma once
 #include "pv_matrix_common.h"
@@ -25,10 +31,11 @@
 struct attn_args {
     const pv_dev_state *st;
     const int32_t *page_table;
-    const float *q;             // [rows][n_q_heads][hd], rotary already applied
+    const uint16_t *q_hi, *q_lo; // [rows][n_q_heads][hd] each, rotary already applied: q = hi + lo
     const uint16_t *pool;
     pv_kv_geom geom;
     int layer, n_q_heads, group, max_chunks;
+    int chunk_shift;            // log2 of the keys per chunk of the partials (8 with one row tile, 7 with two)
     float scale;
     float *part_o;              // [n_kv_heads][MP][max_chunks][32][hd]
     float *part_ml;             // [n_kv_heads][MP][max_chunks][32][2]  (max, sum)
@@ -47,32 +54,44 @@ __device__ inline void split8(const float v[8], uint4 &hi, uint4 &lo)
     hi = make_uint4(h[0], h[1], h[2], h[3]); lo = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
-template <int HD, int R, int HALVES>
-__host__ __device__ constexpr int attn_smem_floats() { return 8 * R * 16 + R * 16 + HALVES * R * 16 + HALVES * R * 16 * (HD + 1); }
+template <int HD>
+__host__ __device__ constexpr int attn_smem_floats() { return 8 * 16 * (HD + 4) + 2 * 8 * 16; }
 
-// One (kv head, 256-key chunk, 32-row group) unit, executed by 8 wavefronts (threads 0..511 of
-// the calling workgroup; every thread of those 8 waves must call it).  HALVES = 2 merges the
-// waves in two side-by-side sequences (needs twice the LDS), HALVES = 1 in one sequence.
-// smem: attn_smem_floats<HD, R, HALVES>() floats of LDS.
-template <int HD, int R, int HALVES>
+// One (kv head, chunk, 32-row group) unit, executed by the 8 wavefronts of the workgroup (all
+// 512 threads must call).  TILES as above; chunk c covers keys c * (256 / TILES) ... .
+// smem: attn_smem_floats<HD>() floats of LDS (more than 64 KiB for HD = 128: dynamic).
+template <int HD, int TILES>
 __device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int mp, int n_mp, float *smem)
 {
-    constexpr int KS = HD / 32, ET = HD / 16, OS = HD + 1;
+    constexpr int KS = HD / 32, ET = HD / 16, OS = HD + 4, NWM = 8 / TILES, CK = 256 / TILES;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, jl = lane & 15, g = lane >> 4;
+    const int rt = wave / NWM, kq = wave % NWM;
     const int len = a.st->len, gamma = a.st->gamma, nkeys = len + gamma;
-    if (c * 256 >= nkeys) return;
+    if (c * CK >= nkeys) return;
     const int nrows = a.group * gamma;
     const pv_kv_geom &gm = a.geom;
     const int sub_shift = gm.page_shift - 4, sub_mask = (1 << sub_shift) - 1;
 
     // this wave's 32 keys: two groups of 16; a group past the end re-reads the first one (it is masked)
-    const int p0 = c * 256 + wave * 32;
+    const int p0 = c * CK + kq * 32;
     const bool has_keys = p0 < nkeys;
-    uint4 kt[2][KS];
+    // this lane's query row: row lane%16 of the wave's 16-row tile
+    const int m = mp * 32 + rt * 16 + jl;
+    const bool live = m < nrows;
+    const int al = live ? m / gamma : 0, j = live ? m - al * gamma : 0;
+    const int lim = live ? len + j : -1;
+    uint4 kt[2][KS], qh[KS], ql[KS];
     uint2 vt[2][ET];
     if (has_keys) {
         const int g0 = p0 >> 4, g1 = (p0 + 16 < nkeys) ? g0 + 1 : g0;
         const int ph0 = a.page_table[g0 >> sub_shift], ph1 = a.page_table[g1 >> sub_shift];
+        // a dead lane reads row 0 of the first head: its scores are masked below (lim = -1)
+        const size_t qoff = ((size_t)j * a.n_q_heads + kvh * a.group + al) * HD + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qh[ks] = *(const uint4 *)(a.q_hi + qoff + ks * 32);
+            ql[ks] = *(const uint4 *)(a.q_lo + qoff + ks * 32);
+        }
         const uint16_t *kb0 = a.pool + pv_kv_block(gm, a.layer, ph0, kvh, 0) + (size_t)(g0 & sub_mask) * 16 * HD;
         const uint16_t *kb1 = a.pool + pv_kv_block(gm, a.layer, ph1, kvh, 0) + (size_t)(g1 & sub_mask) * 16 * HD;
         const uint16_t *vb0 = a.pool + pv_kv_block(gm, a.layer, ph0, kvh, 1) + (size_t)(g0 & sub_mask) * 16 * HD;
@@ -85,117 +104,86 @@ __device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int mp, in
             vt[1][et] = *(const uint2 *)(vb1 + (size_t)(et * 16 + jl) * 16 + 4 * g);
         }
     }
+    // every load above is in flight before the first use: one memory round trip, not one per operand
+    asm volatile("" ::: "memory");
 
-    f32x4 O[R][ET];
-    float mrow[R], lrow[R];
+    f32x4 O[ET];
+    float mrow = -INFINITY, lrow = 0.f;
 #pragma unroll
-    for (int rt = 0; rt < R; ++rt) {
-        mrow[rt] = -INFINITY; lrow[rt] = 0.f;
-#pragma unroll
-        for (int et = 0; et < ET; ++et) O[rt][et] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    }
+    for (int et = 0; et < ET; ++et) O[et] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     if (has_keys) {
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int rt = 0; rt < R; ++rt) {
-            // Q^T operand of this lane's row (row = lane%16 of the 16-row tile), hi and lo
-            const int m = mp * 32 + rt * 16 + jl;
-            const bool live = m < nrows;
-            const int al = live ? m / gamma : 0, j = live ? m - al * gamma : 0;
-            const int lim = live ? len + j : -1;
-            const float *qp = a.q + ((size_t)j * a.n_q_heads + kvh * a.group + al) * HD + g * 8;
-            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < KS; ++ks) {
+            s0 = mfma16(kt[0][ks], qh[ks], s0); s1 = mfma16(kt[1][ks], qh[ks], s1);
+            s0 = mfma16(kt[0][ks], ql[ks], s0); s1 = mfma16(kt[1][ks], ql[ks], s1);
+        }
+        float sv[8];
+        float mx = -INFINITY;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                float v[8];
-                const float4 x0 = *(const float4 *)(qp + ks * 32), x1 = *(const float4 *)(qp + ks * 32 + 4);
-                v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
-                if (!live) {
+        for (int r = 0; r < 4; ++r) {
+            const int pa = p0 + 4 * g + r, pb = pa + 16;
+            sv[r] = (pa <= lim) ? s0[r] * a.scale : -INFINITY;
+            sv[4 + r] = (pb <= lim) ? s1[r] * a.scale : -INFINITY;
+            mx = fmaxf(mx, fmaxf(sv[r], sv[4 + r]));
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const bool none = mx == -INFINITY;                 // no visible key for this row here
+        float pr[8], ps = 0.f;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) v[i] = 0.f;
-                }
-                uint4 qh, ql;
-                split8(v, qh, ql);
-                s0 = mfma16(kt[0][ks], qh, s0); s0 = mfma16(kt[0][ks], ql, s0);
-                s1 = mfma16(kt[1][ks], qh, s1); s1 = mfma16(kt[1][ks], ql, s1);
-            }
-            float sv[8];
-            float mx = -INFINITY;
+        for (int i = 0; i < 8; ++i) { pr[i] = none ? 0.f : __expf(sv[i] - mx); ps += pr[i]; }
+        ps += __shfl_xor(ps, 16, 64);
+        ps += __shfl_xor(ps, 32, 64);
+        lrow = ps; mrow = mx;
+        uint4 ph, pl;
+        split8(pr, ph, pl);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int pa = p0 + 4 * g + r, pb = pa + 16;
-                sv[r] = (pa <= lim) ? s0[r] * a.scale : -INFINITY;
-                sv[4 + r] = (pb <= lim) ? s1[r] * a.scale : -INFINITY;
-                mx = fmaxf(mx, fmaxf(sv[r], sv[4 + r]));
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const bool none = mx == -INFINITY;                 // no visible key for this row here
-            float pr[8], ps = 0.f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { pr[i] = none ? 0.f : expf(sv[i] - mx); ps += pr[i]; }
-            ps += __shfl_xor(ps, 16, 64);
-            ps += __shfl_xor(ps, 32, 64);
-            lrow[rt] = ps; mrow[rt] = mx;
-            uint4 ph, pl;
-            split8(pr, ph, pl);
-#pragma unroll
-            for (int et = 0; et < ET; ++et) {
-                const uint4 va = make_uint4(vt[0][et].x, vt[0][et].y, vt[1][et].x, vt[1][et].y);
-                f32x4 o = {0.f, 0.f, 0.f, 0.f};
-                o = mfma16(va, ph, o);
-                o = mfma16(va, pl, o);
-                O[rt][et] = o;
-            }
+        for (int et = 0; et < ET; ++et) {
+            const uint4 va = make_uint4(vt[0][et].x, vt[0][et].y, vt[1][et].x, vt[1][et].y);
+            f32x4 o = {0.f, 0.f, 0.f, 0.f};
+            o = mfma16(va, ph, o);
+            o = mfma16(va, pl, o);
+            O[et] = o;
         }
     }
 
-    // merge the eight waves in a fixed order: waves 0..3 into buffer 0, waves 4..7 into buffer 1
-    // (both sequences run side by side), then buffer 0 + buffer 1 while writing the partial
-    float (*sh_m)[R * 16] = (float (*)[R * 16])smem;                              // [8][R*16]
-    float *sh_M = smem + 8 * R * 16;                                              // [R*16]
-    float (*sh_l)[R * 16] = (float (*)[R * 16])(sh_M + R * 16);                   // [HALVES][R*16]
-    float (*sh_o)[R * 16][OS] = (float (*)[R * 16][OS])(sh_M + R * 16 + HALVES * R * 16);   // [HALVES][R*16][OS]
-    if (g == 0) {
-#pragma unroll
-        for (int rt = 0; rt < R; ++rt) sh_m[wave][rt * 16 + jl] = mrow[rt];
-    }
+    // merge the NWM waves of each row tile: every wave parks its partial, rescaled to the
+    // tile's common maximum, in LDS; then all threads add the NWM partials in wave order
+    float (*sh_m)[16] = (float (*)[16])smem;                                  // [8][16]
+    float (*sh_l)[16] = (float (*)[16])(smem + 8 * 16);                       // [8][16]
+    float (*sh_o)[16][OS] = (float (*)[16][OS])(smem + 2 * 8 * 16);           // [8][16][OS]
+    if (g == 0) sh_m[wave][jl] = mrow;
     __syncthreads();
-    float f[R];
+    float M = sh_m[rt * NWM][jl];
 #pragma unroll
-    for (int rt = 0; rt < R; ++rt) {
-        const int row = rt * 16 + jl;
-        float M = sh_m[0][row];
+    for (int w = 1; w < NWM; ++w) M = fmaxf(M, sh_m[rt * NWM + w][jl]);
+    const float f = (mrow == -INFINITY) ? 0.f : __expf(mrow - M);
 #pragma unroll
-        for (int w = 1; w < 8; ++w) M = fmaxf(M, sh_m[w][row]);
-        f[rt] = (mrow[rt] == -INFINITY) ? 0.f : expf(mrow[rt] - M);
-        if (wave == 0 && g == 0) sh_M[row] = M;
-    }
-    const int half = (HALVES == 2) ? wave >> 2 : 0, wq = (HALVES == 2) ? wave & 3 : wave;
-    for (int w = 0; w < 8 / HALVES; ++w) {
-        if (wq == w) {
-#pragma unroll
-            for (int rt = 0; rt < R; ++rt) {
-                const int row = rt * 16 + jl;
-#pragma unroll
-                for (int et = 0; et < ET; ++et)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float val = O[rt][et][r] * f[rt];
-                        float *dst = &sh_o[half][row][et * 16 + 4 * g + r];
-                        *dst = (w == 0) ? val : *dst + val;
-                    }
-                if (g == 0) sh_l[half][row] = (w == 0) ? lrow[rt] * f[rt] : sh_l[half][row] + lrow[rt] * f[rt];
-            }
-        }
-        __syncthreads();
-    }
+    for (int et = 0; et < ET; ++et)
+        *(float4 *)&sh_o[wave][jl][et * 16 + 4 * g] = make_float4(O[et][0] * f, O[et][1] * f, O[et][2] * f, O[et][3] * f);
+    if (g == 0) sh_l[wave][jl] = lrow * f;
+    __syncthreads();
     const size_t unit = ((size_t)kvh * n_mp + mp) * a.max_chunks + c;
     float *po = a.part_o + unit * 32 * HD;
-    for (int i = threadIdx.x; i < R * 16 * HD; i += 512) po[i] = (HALVES == 2) ? sh_o[0][i / HD][i % HD] + sh_o[HALVES - 1][i / HD][i % HD] : sh_o[0][i / HD][i % HD];
-    if (threadIdx.x < R * 16) {
+    for (int i = threadIdx.x; i < TILES * 16 * (HD / 4); i += 512) {
+        const int row = i / (HD / 4), c4 = i - row * (HD / 4), t = row >> 4, r = row & 15;
+        float4 acc = *(const float4 *)&sh_o[t * NWM][r][4 * c4];
+#pragma unroll
+        for (int w = 1; w < NWM; ++w) {
+            const float4 v = *(const float4 *)&sh_o[t * NWM + w][r][4 * c4];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        *(float4 *)(po + (size_t)row * HD + 4 * c4) = acc;
+    }
+    if (threadIdx.x < TILES * 16) {
+        const int t = threadIdx.x >> 4, r = threadIdx.x & 15;
+        float Mr = sh_m[t * NWM][r], L = sh_l[t * NWM][r];
+#pragma unroll
+        for (int w = 1; w < NWM; ++w) { Mr = fmaxf(Mr, sh_m[t * NWM + w][r]); L += sh_l[t * NWM + w][r]; }
         float *pm = a.part_ml + (unit * 32 + threadIdx.x) * 2;
-        pm[0] = sh_M[threadIdx.x]; pm[1] = (HALVES == 2) ? sh_l[0][threadIdx.x] + sh_l[HALVES - 1][threadIdx.x] : sh_l[0][threadIdx.x];
+        pm[0] = Mr; pm[1] = L;
     }
 }
 
@@ -210,20 +198,25 @@ __device__ inline void attn_merge_unit(const attn_args &a, int j, int aq, int mp
     constexpr int NG = NT / TPC;           // chunk groups working side by side
     const int gamma = a.st->gamma;
     const int kvh = aq / a.group, al = aq - kvh * a.group, m = al * gamma + j, mp = m >> 5, row = m & 31;
-    const int nchunks = (a.st->len + gamma + 255) >> 8;
+    const int nchunks = (a.st->len + gamma + (1 << a.chunk_shift) - 1) >> a.chunk_shift;
     const size_t unit0 = ((size_t)kvh * mp_count + mp) * a.max_chunks;
     float *sh_m = smem;                                              // [NT]
     float (*sh_acc)[TPC][5] = (float (*)[TPC][5])(smem + NT);        // [NG][TPC][5]
-    // global max over chunks (each thread looks at chunks t, t+256, ...)
+    // global max over chunks: with few chunks every thread reads them all (broadcast loads, no
+    // barrier); with many, each thread looks at chunks t, t+NT, ... and a tree in LDS finishes
     float M = -INFINITY;
-    for (int c = tid; c < nchunks; c += NT) M = fmaxf(M, a.part_ml[((unit0 + c) * 32 + row) * 2]);
-    sh_m[tid] = M;
-    __syncthreads();
-    for (int s2 = NT / 2; s2 > 0; s2 >>= 1) {
-        if ((int)tid < s2) sh_m[tid] = fmaxf(sh_m[tid], sh_m[tid + s2]);
+    if (nchunks <= 32) {
+        for (int c = 0; c < nchunks; ++c) M = fmaxf(M, a.part_ml[((unit0 + c) * 32 + row) * 2]);
+    } else {
+        for (int c = tid; c < nchunks; c += NT) M = fmaxf(M, a.part_ml[((unit0 + c) * 32 + row) * 2]);
+        sh_m[tid] = M;
         __syncthreads();
+        for (int s2 = NT / 2; s2 > 0; s2 >>= 1) {
+            if ((int)tid < s2) sh_m[tid] = fmaxf(sh_m[tid], sh_m[tid + s2]);
+            __syncthreads();
+        }
+        M = sh_m[0];
     }
-    M = sh_m[0];
     const int t = tid % TPC, cg = tid / TPC;
     float acc[4] = {0.f, 0.f, 0.f, 0.f}, L = 0.f;
     for (int c = cg; c < nchunks; c += NG) {

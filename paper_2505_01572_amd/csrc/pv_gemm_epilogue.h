@@ -14,7 +14,7 @@ struct gemm_args {
     // RMSNorm scale of the input rows (QKV, SWIGLU, LMHEAD)
     const float *ssq; int ssq_parts; float inv_d, eps;
     // QKV
-    float *q; uint16_t *pool; const int32_t *page_table; const float2 *rope; pv_kv_geom geom;
+    uint16_t *q_hi, *q_lo; uint16_t *pool; const int32_t *page_table; const float2 *rope; pv_kv_geom geom;
     int layer, n_q_heads, q_strips, k_strips;
     // RESID
     float *x; const uint16_t *gain_next; float *ssq_out; uint16_t *xop_out; int d;
@@ -138,7 +138,13 @@ __device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 
             }
             if (live) {
                 if (strip < a.q_strips) {
-                    *(float4 *)(a.q + ((size_t)j * a.n_q_heads + h) * hd + e + side * half) = make_float4(o[0], o[1], o[2], o[3]);
+                    // queries leave as bf16 hi + lo pairs, the form attention feeds to the matrix cores
+                    uint16_t qh[4], ql[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) { qh[r] = bf16_rne(o[r]); ql[r] = bf16_rne(o[r] - pv_bf16_to_f32(qh[r])); }
+                    const size_t qo = ((size_t)j * a.n_q_heads + h) * hd + e + side * half;
+                    *(uint2 *)(a.q_hi + qo) = make_uint2(qh[0] | ((uint32_t)qh[1] << 16), qh[2] | ((uint32_t)qh[3] << 16));
+                    *(uint2 *)(a.q_lo + qo) = make_uint2(ql[0] | ((uint32_t)ql[1] << 16), ql[2] | ((uint32_t)ql[3] << 16));
                 } else {
                     const int kvh = h - a.n_q_heads;
                     uint16_t *kp = a.pool + pv_kv_block(gm, a.layer, p.phys, kvh, 0) + pv_k_off(gm, tok, e + side * half);

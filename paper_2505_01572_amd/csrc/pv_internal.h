@@ -127,6 +127,7 @@ int pv_mat_run_block(pv_cache *c, hipStream_t s);        // pv_kernels_matrix.hi
 int pv_mat_repack(const pv_model *m, const pv_tensor_ref &t, int kind, int64_t row_begin, int64_t row_count, hipStream_t s);
 size_t pv_mat_part_floats(const pv_model *m, int rows_cap, int max_tokens);
 size_t pv_attn_part_floats(const pv_model *m, int rows_cap, int max_tokens);
+int pv_mat_attention_init(int head_dim);
 int pv_mat_attention(pv_cache *c, int layer, int rows, float *part, uint16_t *xop_o, hipStream_t s);
 int pv_common_export(pv_cache *c, void *d_out, hipStream_t s);   // gathers logical K/V into d_out
 void pv_set_error(const char *fmt, ...);

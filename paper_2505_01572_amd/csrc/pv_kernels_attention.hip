@@ -1,12 +1,12 @@
 // Kernel wrappers of the attention units (pv_attention_body.h) for the per-kernel step sequence.
 #include "pv_attention_body.h"
 
-template <int HD, int R>
+template <int HD, int TILES>
 __global__ void __launch_bounds__(512)
 k_attn(const attn_args a)
 {
-    __shared__ float smem[attn_smem_floats<HD, R, 2>()];
-    attn_chunk<HD, R, 2>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z, smem);
+    extern __shared__ float4 smem4[];               // attn_smem_floats<HD>() floats: above the static limit for HD = 128
+    attn_chunk<HD, TILES>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z, (float *)smem4);
 }
 
 template <int NB, int HD>
@@ -23,7 +23,7 @@ k_attn_merge(const attn_args a, int mp_count)
 size_t pv_attn_part_floats(const pv_model *m, int rows_cap, int max_tokens)
 {
     const pv_model_config &f = m->cfg;
-    const int group = f.n_q_heads / f.n_kv_heads, mp = (group * rows_cap + 31) / 32, chunks = (max_tokens + 255) / 256;
+    const int group = f.n_q_heads / f.n_kv_heads, mp = (group * rows_cap + 31) / 32, chunks = (max_tokens + 127) / 128;   // the finer of the two chunkings
     return (size_t)f.n_kv_heads * mp * chunks * 32 * (f.head_dim + 2);
 }
 
@@ -32,23 +32,52 @@ static int launch(pv_cache *c, attn_args &a, int rows, hipStream_t s)
 {
     const pv_model_config &f = c->m->cfg;
     const int nrows = a.group * rows, mp = (nrows + 31) / 32;
-    const dim3 grid(a.max_chunks, f.n_kv_heads, mp);
-    if (nrows <= 16) k_attn<HD, 1><<<grid, 512, 0, s>>>(a);
-    else k_attn<HD, 2><<<grid, 512, 0, s>>>(a);
+    // up to 16 query rows per kv head: 256-key chunks, eight waves of 32 keys each; more rows:
+    // 128-key chunks, the waves split into two 16-row tiles x four 32-key groups
+    constexpr size_t lds = attn_smem_floats<HD>() * sizeof(float);
+    if (nrows <= 16) {
+        a.chunk_shift = 8; a.max_chunks = (c->max_tokens + 255) / 256;
+        k_attn<HD, 1><<<dim3(a.max_chunks, f.n_kv_heads, mp), 512, lds, s>>>(a);
+    } else {
+        a.chunk_shift = 7; a.max_chunks = (c->max_tokens + 127) / 128;
+        k_attn<HD, 2><<<dim3(a.max_chunks, f.n_kv_heads, mp), 512, lds, s>>>(a);
+    }
     PV_HIP(hipGetLastError());
     k_attn_merge<NB, HD><<<dim3(rows, f.n_q_heads), 256, 0, s>>>(a, mp);
     PV_HIP(hipGetLastError());
     return PV_OK;
 }
 
-// q (fp32, rotated) -> xop_o; part = scratch of pv_attn_part_floats floats
+template <int HD>
+static int allow_lds()
+{
+    constexpr int lds = attn_smem_floats<HD>() * (int)sizeof(float);
+    PV_HIP(hipFuncSetAttribute((const void *)k_attn<HD, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    PV_HIP(hipFuncSetAttribute((const void *)k_attn<HD, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    return PV_OK;
+}
+
+// once per device before the first launch (and outside any stream capture): the attention
+// kernels use more dynamic LDS than the default limit
+int pv_mat_attention_init(int head_dim)
+{
+    switch (head_dim) {
+    case 32: return allow_lds<32>();
+    case 64: return allow_lds<64>();
+    case 128: return allow_lds<128>();
+    default: pv_set_error("matrix path: unsupported head_dim %d", head_dim); return PV_EINVAL;
+    }
+}
+
+// q (bf16 hi + lo, rotated) -> xop_o; part = scratch of pv_attn_part_floats floats
 int pv_mat_attention(pv_cache *c, int layer, int rows, float *part, uint16_t *xop_o, hipStream_t s)
 {
     const pv_model_config &f = c->m->cfg;
     attn_args a;
-    a.st = c->ws.state; a.page_table = c->ws.page_table; a.q = c->ws.q; a.pool = (const uint16_t *)c->d_pool;
+    a.st = c->ws.state; a.page_table = c->ws.page_table; a.q_hi = (const uint16_t *)c->ws.q; a.q_lo = a.q_hi + (size_t)c->rows_cap * f.n_q_heads * f.head_dim; a.pool = (const uint16_t *)c->d_pool;
     a.geom = pv_geom(c); a.layer = layer; a.n_q_heads = f.n_q_heads; a.group = f.n_q_heads / f.n_kv_heads;
-    a.max_chunks = (c->max_tokens + 255) / 256;
+    a.max_chunks = (c->max_tokens + 127) / 128;        // sizes the partial arrays; the launch sets the chunking in use
+    a.chunk_shift = 7;
     a.scale = 1.0f / sqrtf((float)f.head_dim);
     const int mp_cap = (a.group * c->rows_cap + 31) / 32;
     a.part_o = part;

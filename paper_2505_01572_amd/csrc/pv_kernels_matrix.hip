@@ -247,7 +247,7 @@ static int run_block(pv_cache *c, hipStream_t s)
     gemm_args g = {};
     int prc;
     g.st = c->ws.state; g.inv_d = 1.0f / (float)d; g.eps = (float)f.rms_eps; g.ssq_parts = d / 16;
-    g.q = c->ws.q; g.pool = (uint16_t *)c->d_pool; g.page_table = c->ws.page_table; g.rope = c->ws.rope; g.geom = pv_geom(c);
+    g.q_hi = (uint16_t *)c->ws.q; g.q_lo = g.q_hi + (size_t)c->rows_cap * qd; g.pool = (uint16_t *)c->d_pool; g.page_table = c->ws.page_table; g.rope = c->ws.rope; g.geom = pv_geom(c);
     g.n_q_heads = f.n_q_heads; g.q_strips = qd / 16; g.k_strips = kvd / 16;
     g.x = c->ws.x; g.d = d; g.xop_act = mw.xop_d; g.F = F;
     g.logits = c->ws.logits; g.pmax_val = mw.pmax_val; g.pmax_idx = mw.pmax_idx; g.vocab = f.vocab;
