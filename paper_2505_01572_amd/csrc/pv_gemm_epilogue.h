@@ -44,34 +44,43 @@ __device__ inline void emit_x(int lane, int rows, int strip, int d, const float 
     }
 }
 
-// rsqrt(mean(x_j^2) + eps) for row j = lane % 16 from the [parts][16] partial sums, summed in a
-// fixed order.  All loads are independent (a serial chain of L2 round trips would cost far more
-// than the weight stream it sits beside): lane l reads float4 number l, l+64, ... so it always
-// sees rows 4*(l%4)..+3; lanes with equal l%4 are then combined and the result redistributed.
-__device__ inline float row_rscale(const float *ssq, int parts, float inv_d, float eps, int lane)
+// Sum of squares of the input rows from the [parts][16] per-strip partial sums, first level,
+// in two halves so that the caller can put its main loop between issue and use.  Thread `tid`
+// of `nthreads` takes the float4 groups tid, tid+nthreads, ... (all loads independent: a serial
+// chain of L2 round trips would cost more than the weight stream it sits beside).
+struct ssq_loads { float4 v[2]; };
+
+__device__ inline void ssq_issue(const float *ssq, int parts, int tid, int nthreads, ssq_loads &L)
+{
+    const float4 *q = (const float4 *)ssq;
+    const int n4 = parts * 4;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) { const int i = tid + u * nthreads; L.v[u] = q[i < n4 ? i : 0]; }   // no branch: masked in ssq_finish
+}
+
+// Second half: add up (plus any groups beyond the first two per thread), then combine the lanes
+// of the wave that hold the same rows (equal lane % 4).  On return lanes 0..3 hold the wave's
+// sums for rows 4*lane .. 4*lane+3.
+__device__ inline float4 ssq_finish(const float *ssq, int parts, int tid, int nthreads, const ssq_loads &L)
 {
     const float4 *q = (const float4 *)ssq;
     const int n4 = parts * 4;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int i0 = lane; i0 < n4; i0 += 64 * 8) {
-        float4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) { const int i = i0 + u * 64; v[u] = i < n4 ? q[i] : make_float4(0.f, 0.f, 0.f, 0.f); }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+    for (int u = 0; u < 2; ++u) {
+        if (tid + u * nthreads < n4) { s.x += L.v[u].x; s.y += L.v[u].y; s.z += L.v[u].z; s.w += L.v[u].w; }
     }
+    for (int i = tid + 2 * nthreads; i < n4; i += nthreads) { const float4 v = q[i]; s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w; }
 #pragma unroll
     for (int o = 4; o <= 32; o <<= 1) {
         s.x += __shfl_xor(s.x, o, 64); s.y += __shfl_xor(s.y, o, 64); s.z += __shfl_xor(s.z, o, 64); s.w += __shfl_xor(s.w, o, 64);
     }
-    const int j = lane & 15, src = j >> 2;
-    const float t0 = __shfl(s.x, src, 64), t1 = __shfl(s.y, src, 64), t2 = __shfl(s.z, src, 64), t3 = __shfl(s.w, src, 64);
-    const float tot = (j & 3) == 0 ? t0 : (j & 3) == 1 ? t1 : (j & 3) == 2 ? t2 : t3;
-    return 1.0f / sqrtf(tot * inv_d + eps);
+    return s;
 }
 
-// What an epilogue needs from memory.  The owner wave fetches it before it starts streaming so
-// that after the reduction only arithmetic and stores remain.
+// What an epilogue needs from memory (rj is filled in after the reduction from the waves' sums
+// of squares).  The owner wave fetches it while its first weight batch is in flight and parks it
+// in LDS, so that after the reduction only arithmetic and stores remain.
 struct epi_pre {
     float rj;
     int rows, pos, phys;
@@ -83,14 +92,12 @@ struct epi_pre {
 template <int EPI>
 __device__ inline void epi_prefetch(const gemm_args &a, int strip, int lane, epi_pre &p)
 {
-    constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
     const int j = lane & 15, g = lane >> 4;
     p.rj = 1.f; p.pos = 0; p.phys = 0;
     p.xo = make_float4(0.f, 0.f, 0.f, 0.f); p.gn = make_uint2(0u, 0u);
 #pragma unroll
     for (int r = 0; r < 4; ++r) p.cs[r] = make_float2(1.f, 0.f);
     p.rows = a.st->gamma;
-    if (NORM) p.rj = row_rscale(a.ssq, a.ssq_parts, a.inv_d, a.eps, lane);
     if (EPI == EPI_RESID) {
         const int n = strip * 16 + 4 * g;
         if (j < p.rows) p.xo = *(const float4 *)(a.x + (size_t)j * a.d + n);
@@ -106,6 +113,36 @@ __device__ inline void epi_prefetch(const gemm_args &a, int strip, int lane, epi
                 for (int r = 0; r < 4; ++r) p.cs[r] = a.rope[(size_t)j * (a.geom.head_dim >> 1) + e + r];
             }
         }
+    }
+}
+
+// LDS hand-over of the prefetched inputs across the weight stream (they would otherwise occupy
+// registers for the whole K loop): only the fields the epilogue kind reads travel.
+template <int EPI>
+__device__ inline void epi_park(epi_pre *slot, const epi_pre &p)
+{
+    slot->rows = p.rows;
+    if (EPI == EPI_RESID) { slot->xo = p.xo; slot->gn = p.gn; }
+    if (EPI == EPI_QKV) {
+        slot->pos = p.pos; slot->phys = p.phys;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) slot->cs[r] = p.cs[r];
+    }
+}
+
+template <int EPI>
+__device__ inline void epi_unpark(const epi_pre *slot, epi_pre &p)
+{
+    p.rj = 1.f; p.pos = 0; p.phys = 0;
+    p.xo = make_float4(0.f, 0.f, 0.f, 0.f); p.gn = make_uint2(0u, 0u);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) p.cs[r] = make_float2(1.f, 0.f);
+    p.rows = slot->rows;
+    if (EPI == EPI_RESID) { p.xo = slot->xo; p.gn = slot->gn; }
+    if (EPI == EPI_QKV) {
+        p.pos = slot->pos; p.phys = slot->phys;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) p.cs[r] = slot->cs[r];
     }
 }
 

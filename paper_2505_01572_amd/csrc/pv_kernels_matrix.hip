@@ -135,7 +135,7 @@ __global__ void k_to_operand(const pv_dev_state *st, const float *src, uint16_t 
 // The streaming GEMM: one workgroup per strip, NW waves split K.
 // ------------------------------------------------------------------------------------------
 template <int NB, int EPI, int NW>
-__global__ void __launch_bounds__(NW * 64)
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NB == 1 ? 8 : 4)))   // <= 64 VGPRs: two 16-wave workgroups per CU
 k_gemm(const gemm_args a)
 {
     constexpr int U = 4;
@@ -146,12 +146,46 @@ k_gemm(const gemm_args a)
     const uint4 *B = a.xop + lane;
     const uint4 *B2 = a.xop + (size_t)KT * 64 + lane;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
 
-    epi_pre pre;
-    if (wave == 0) epi_prefetch<EPI>(a, strip, lane, pre);
+    // RMSNorm of the input rows: every wave takes its share of the per-strip sums of squares; the
+    // loads go out ahead of the weight stream and are folded in behind it
+    ssq_loads sl;
+    if (NORM) ssq_issue(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl);
 
     // Few registers on purpose: latency is hidden by many resident workgroups per CU.
+    __shared__ f32x4 red[NW][64];
+    __shared__ float ssq_s[NW][16];
+    __shared__ epi_pre pre_s[64];
     int t = kb;
+    {   // first batch peeled: the sums of squares are folded in while its loads are in flight
+        uint4 ra[U], rb[U], rc[U];
+        const bool first = t + U <= ke;
+        if (first) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                ra[u] = A[(size_t)(t + u) * 64]; rb[u] = B[(size_t)(t + u) * 64];
+                if (NB == 2) rc[u] = B2[(size_t)(t + u) * 64];
+            }
+        }
+        if (NORM) {
+            const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl);
+            if (lane < 4) *(float4 *)&ssq_s[wave][4 * lane] = s4;
+        }
+        if (wave == 0) {                            // behind the first batch's loads, ahead of its use
+            epi_pre pre;
+            epi_prefetch<EPI>(a, strip, lane, pre);
+            epi_park<EPI>(&pre_s[lane], pre);
+        }
+        if (first) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                acc = mfma16(ra[u], rb[u], acc);
+                if (NB == 2) acc = mfma16(ra[u], rc[u], acc);
+            }
+            t += U;
+        }
+    }
     for (; t + U <= ke; t += U) {
         uint4 ra[U], rb[U], rc[U];
 #pragma unroll
@@ -170,14 +204,21 @@ k_gemm(const gemm_args a)
         if (NB == 2) acc = mfma16(A[(size_t)t * 64], B2[(size_t)t * 64], acc);
     }
 
-    // sum the NW K-slices in wave order
-    __shared__ f32x4 red[NW][64];
+    // sum the NW K-slices (and the NW shares of the sums of squares) in wave order
     red[wave][lane] = acc;
     __syncthreads();
     if (wave != 0) return;
     f32x4 sum = red[0][lane];
 #pragma unroll
     for (int w = 1; w < NW; ++w) { const f32x4 p = red[w][lane]; sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3]; }
+    epi_pre pre;
+    epi_unpark<EPI>(&pre_s[lane], pre);
+    if (NORM) {
+        float tot = ssq_s[0][lane & 15];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) tot += ssq_s[w][lane & 15];
+        pre.rj = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+    }
     epi_apply<NB, EPI>(a, strip, lane, sum, pre);
 }
 
