@@ -219,6 +219,7 @@ __device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 
             const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
             if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
         }
-        if (lane < 16) { a.pmax_val[strip * 16 + j] = bv; a.pmax_idx[strip * 16 + j] = bi; }
+        // candidates are stored row-major ([16][vocab/16]) so that the reduction over strips reads contiguously
+        if (lane < 16) { const size_t o = (size_t)j * (a.vocab >> 4) + strip; a.pmax_val[o] = bv; a.pmax_idx[o] = bi; }
     }
 }

@@ -28,7 +28,7 @@
 struct mat_ws {                 // carved out of pv_ws::part
     uint16_t *xop_a, *xop_o, *xop_f, *xop_d;   // operands: QKV in (K=d), O in (K=qd), gate/up in (K=d), down in (K=F)
     float *ssq0, *ssq1;                         // [d/16][16] partial sums of x^2
-    float *pmax_val; int32_t *pmax_idx;         // [vocab/16][16] per-strip arg-max candidates
+    float *pmax_val; int32_t *pmax_idx;         // [16][vocab/16] per-strip arg-max candidates, row-major
     float *attn_part;                           // attention chunk partials
 };
 
@@ -229,9 +229,14 @@ k_argmax_parts(pv_dev_state *st, const float *pv, const int32_t *pi, int strips)
     const int j = blockIdx.x;
     if (j >= st->gamma) return;
     float bv = -INFINITY; int bi = 0x7fffffff;
-    for (int s = threadIdx.x; s < strips; s += 256) {
-        const float v = pv[s * 16 + j]; const int i = pi[s * 16 + j];
-        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+    const float *rv = pv + (size_t)j * strips; const int32_t *ri = pi + (size_t)j * strips;
+    for (int s0 = threadIdx.x; s0 < strips; s0 += 256 * 8) {          // eight independent loads in flight per thread
+        float v[8]; int i[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { const int s = s0 + 256 * u, sc = s < strips ? s : s0; v[u] = rv[sc]; i[u] = ri[sc]; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + 256 * u < strips && (v[u] > bv || (v[u] == bv && i[u] < bi))) { bv = v[u]; bi = i[u]; }
     }
     __shared__ float sv[256];
     __shared__ int si[256];
