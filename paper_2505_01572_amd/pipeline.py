@@ -209,6 +209,20 @@ def closed_form_tokens_per_step(alpha, gamma):
     return (1.0 - rho) + rho * geo
 
 
+def load_stage_model(pv, pv_inputs, shp, max_gamma=16):
+    """A library model of the given shape with its seeded synthetic weights, generated and
+    uploaded chunk by chunk through one pinned host buffer."""
+    import torch
+    m = pv.Model(shp, max_gamma=max_gamma)
+    pinned = torch.empty(m.staging_bytes // 2, dtype=torch.int16, pin_memory=True)
+    scratch = pinned.numpy().view(m.np_dtype)
+    for kind, layer in pv_inputs.iter_tensors(shp):
+        cols = pv_inputs.tensor_shape(shp, kind)[-1]
+        for r0, rows in pv_inputs.iter_row_chunks(shp, kind, layer, m.chunk_rows(cols), scratch=scratch):
+            m.load_weights(kind, layer, r0, rows)
+    return m
+
+
 def main():
     """Config-5 style run: python -m paper_2505_01572_amd.pipeline [--stages 1b,8b,70b_v128k] [--tokens 256]."""
     import argparse
@@ -239,13 +253,7 @@ def main():
     stages = []
     for i, shp in enumerate(shapes):
         t0 = time.time()
-        m = pv.Model(shp, max_gamma=16)
-        pinned = torch.empty(m.staging_bytes // 2, dtype=torch.int16, pin_memory=True)
-        scratch = pinned.numpy().view(m.np_dtype)
-        for kind, layer in pv_inputs.iter_tensors(shp):
-            cols = pv_inputs.tensor_shape(shp, kind)[-1]
-            for r0, rows in pv_inputs.iter_row_chunks(shp, kind, layer, m.chunk_rows(cols), scratch=scratch):
-                m.load_weights(kind, layer, r0, rows)
+        m = load_stage_model(pv, pv_inputs, shp)
         c = pv.Cache(m, a.prefix + span)
         c.prefill(prompt)
         print(f"[pipeline] stage {i} ({shp.name}) ready in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)

@@ -72,3 +72,34 @@ def test_three_stage_pipeline_is_lossless(pvlib):
         fin.cache.rollback(T0 + fin.m)
         n, nxt = fin.cache.verify(T0 + fin.m, [target[fin.m]])
         assert (n, nxt) == (1, target[fin.m + 1])
+
+
+def test_sync_speculative_decoding_on_real_caches(pvlib):
+    """Draft-then-verify with two small real models: the output is the target model's own greedy
+    decoding, and afterwards the target cache holds exactly the K/V of prompt + output (compared
+    with a fresh cache that prefilled that sequence), i.e. readmit / rollback left no trace."""
+    from gpu_helpers import gpu_model
+    from paper_2505_01572_amd import drivers as dr, pipeline as pl
+    T0, n_draft, n_tokens = 48, 7, 50
+    prompt = pv_inputs.uniform_tokens(2, T0, 512)
+    gm_t = gpu_model(S2)
+    cd, ct = pvlib.Cache(gpu_model(S0), T0 + n_tokens + 64), pvlib.Cache(gm_t, T0 + n_tokens + 64)
+    cd.prefill(prompt); ct.prefill(prompt)
+    target, _, _ = dr.autoregressive(ct, T0, ct.pending, n_tokens + 4 * (n_draft + 1))
+    u = pv_inputs.unit_draws(4, len(target), stream=11)
+    res = dr.speculative_sync(pl.Stage(0, cd, 0.7, 1), ct, T0, np.array(target), u, 512, n_tokens, n_draft)
+    m = res["tokens"]
+    assert m >= n_tokens and res["output"] == [int(t) for t in target[:m]]
+    assert 1.0 < res["tokens_per_round"] <= n_draft + 1 and 0.4 < res["alpha_trials"] < 0.95
+    assert ct.state() == (T0 + m, int(target[m]))
+    fresh = pvlib.Cache(gm_t, T0 + m + 16)
+    fresh.prefill(np.concatenate([prompt, np.array(target[:m], dtype=np.int32)]))
+    a, b = ct.export(), fresh.export()
+    # same tokens at the same positions; block shapes differ between the two runs (rows per step),
+    # so equality is up to the 1-ulp bf16 flips of a different summation order
+    assert a.shape == b.shape
+    fa, fb = pv_inputs.bf16_bits_to_f32(a), pv_inputs.bf16_bits_to_f32(b)
+    assert np.mean(fa != fb) < 0.05 and np.abs(fa - fb).max() <= 2.0 ** -6 * np.abs(fb).max()
+    # decoding on from the speculative run's cache reproduces the reference continuation
+    n, nxt = ct.verify(T0 + m, [target[m]])
+    assert (n, nxt) == (1, target[m + 1])

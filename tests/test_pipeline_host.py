@@ -81,3 +81,52 @@ def test_closed_form_helper_matches_eq1_values():
     assert abs(pl.closed_form_tokens_per_step(0.7, 8) - 1.92741) < 1e-4
     assert abs(pl.closed_form_tokens_per_step(0.6, 8) - 1.55656) < 1e-4
     assert pl.closed_form_tokens_per_step(0.5, 1) > 1.0
+
+
+# ---- synchronous speculative decoding and the autoregressive drive (drivers.py) ----
+
+@pytest.mark.parametrize("level,n_draft", [(0.0, 4), (0.5, 3), (0.8, 7), (1.0, 5)])
+def test_sync_speculative_decoding_is_lossless_and_geometric(level, n_draft):
+    from paper_2505_01572_amd import drivers as dr
+    vocab, T0, n_tokens = 1000, 32, 4000
+    rng = np.random.default_rng(17)
+    target = rng.integers(0, vocab, n_tokens + 4 * (n_draft + 1) + 16)
+    u = rng.random(len(target))
+    d = pl.Stage(0, FakeCache(T0, 0.0, vocab), level, 1)
+    tc = FakeCache(T0, 0.0, vocab)
+    res = dr.speculative_sync(d, tc, T0, target, u, vocab, n_tokens, n_draft)
+    assert res["output"] == [int(t) for t in target[:res["tokens"]]]
+    assert res["tokens"] >= n_tokens and len(tc) == T0 + res["tokens"]
+    assert tc.pending == int(target[res["tokens"]])
+    # tokens per round follow the truncated geometric law behind Eq. 5's numerator
+    expect = dr.pipespec_closed_form(level, n_draft) if level < 1.0 else n_draft + 1.0
+    assert abs(res["tokens_per_round"] - expect) < 0.06 * expect + 0.02
+    if 0.0 < level < 1.0:
+        assert abs(res["alpha_trials"] - level) < 0.03
+    # every round cost n_draft draft steps and one target step
+    assert res["draft_steps"] == res["rounds"] * n_draft and tc.calls["verify"] == res["rounds"]
+
+
+def test_autoregressive_drive_and_closed_forms():
+    from paper_2505_01572_amd import drivers as dr
+
+    class Echo(FakeCache):           # next token = (last input + 1) % vocab
+        def verify(self, prefix_len, draft, stream=None):
+            n, _ = super().verify(prefix_len, draft, stream)
+            self.pending = (int(draft[0]) + 1) % self.vocab
+            return n, self.pending
+
+    c = Echo(10, 0.0, 50)
+    out, secs, steps = dr.autoregressive(c, 10, 7, 20)
+    assert out == [(7 + i) % 50 for i in range(21)] and steps == 20 and len(c) == 30
+    # Eq. 5 against its parts; Eq. 6 is its numerator; both reduce to 1 token per step at alpha = 0
+    assert dr.sd_closed_form(0.0, 5, 4.0) == pytest.approx(1.0 / (5 / 4.0 + 1.0))
+    assert dr.sd_closed_form(0.5, 3, 1e12) == pytest.approx(1.875)
+    assert dr.pipespec_closed_form(0.5, 3) == pytest.approx(1 + 0.5 + 0.25 + 0.125)
+    assert dr.pipespec_closed_form(1.0, 7) == 8.0
+    # the product's closed forms agree with the independently written ones the oracle pins to Monte Carlo
+    from oracle import ratecheck as rc
+    for al, g, cc in ((0.3, 4, 2.0), (0.7, 8, 5.5), (0.9, 7, 12.0)):
+        assert dr.sd_closed_form(al, g, cc) == pytest.approx(rc.sd_speedup(al, g, cc))
+        assert dr.pipespec_closed_form(al, g) == pytest.approx(rc.pipespec_high_alpha(al, g))
+        assert pl.closed_form_tokens_per_step(al, g) == pytest.approx(rc.expected_tokens(al, g))
