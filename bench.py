@@ -137,7 +137,7 @@ def main():
     K, W = a.steps, a.warmup
     n_steps = K + W
 
-    model = load_model(pv, pv_inputs, shape, max_gamma=16)
+    model = load_model(pv, pv_inputs, shape, max_gamma=16 if gamma <= 16 else 64)
     max_tokens = T0 + (2 * n_steps + 2) * gamma + 16
     cache = pv.Cache(model, max_tokens)
     if os.environ.get("PV_BENCH_GRAPHS") == "0":     # comparison runs: plain launches instead of graph replay

@@ -50,7 +50,6 @@ static int check_config(const pv_model_config *c)
     if (c->head_dim % 2 || c->head_dim > 256) { pv_set_error("head_dim must be even and <= 256"); return PV_EINVAL; }
     if (c->dtype != PV_F32 && c->dtype != PV_BF16) { pv_set_error("bad dtype"); return PV_EINVAL; }
     if (!is_pow2(c->page_tokens)) { pv_set_error("page_tokens must be a power of two"); return PV_EINVAL; }
-    if (resolve_path(c) >= PV_PATH_MATRIX && c->max_gamma > 16) { pv_set_error("matrix path: max_gamma must be <= 16"); return PV_EINVAL; }
     if (c->max_gamma < 1 || c->max_gamma > PV_MAX_ROWS) { pv_set_error("max_gamma must be in [1, %d]", PV_MAX_ROWS); return PV_EINVAL; }
     if (!(c->rms_eps > 0) || !(c->rope_base > 1)) { pv_set_error("bad rms_eps / rope_base"); return PV_EINVAL; }
     const int path = resolve_path(c);

@@ -27,17 +27,19 @@ struct gemm_args {
 
 // Shared tail of everything that produces a new residual stream value: store x, the partial
 // sum of squares of this 16-feature strip, and (gain * x) as the next GEMM's operand.
+// Rows come in column tiles of 16 (ct = 0 .. ): row j = 16 * ct + lane % 16; the sums of
+// squares are kept per tile as [ct][d/16 strips][16].
 template <int NB>
 __device__ inline void emit_x(int lane, int rows, int strip, int d, const float v[4], uint2 gain4,
-                              float *x, float *ssq, uint16_t *xop)
+                              float *x, float *ssq, uint16_t *xop, int ct = 0)
 {
-    const int j = lane & 15, g = lane >> 4, n = strip * 16 + 4 * g;
+    const int jl = lane & 15, j = ct * 16 + jl, g = lane >> 4, n = strip * 16 + 4 * g;
     const bool live = j < rows;
     if (live) *(float4 *)(x + (size_t)j * d + n) = make_float4(v[0], v[1], v[2], v[3]);
     float ss = live ? (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]) : 0.f;
     ss += __shfl_xor(ss, 16, 64);
     ss += __shfl_xor(ss, 32, 64);
-    if (lane < 16) ssq[strip * 16 + j] = ss;
+    if (lane < 16) ssq[((size_t)ct * (d >> 4) + strip) * 16 + jl] = ss;
     if (live) {
         const float y[4] = {v[0] * pv_bf16_to_f32((uint16_t)(gain4.x & 0xffffu)), v[1] * pv_bf16_to_f32((uint16_t)(gain4.x >> 16)),
                             v[2] * pv_bf16_to_f32((uint16_t)(gain4.y & 0xffffu)), v[3] * pv_bf16_to_f32((uint16_t)(gain4.y >> 16))};
@@ -91,9 +93,9 @@ struct epi_pre {
 };
 
 template <int EPI>
-__device__ inline void epi_prefetch(const gemm_args &a, int strip, int lane, epi_pre &p)
+__device__ inline void epi_prefetch(const gemm_args &a, int strip, int lane, epi_pre &p, int ct = 0)
 {
-    const int j = lane & 15, g = lane >> 4;
+    const int j = ct * 16 + (lane & 15), g = lane >> 4;
     p.rj = 1.f; p.pos = 0; p.phys = 0;
     p.xo = make_float4(0.f, 0.f, 0.f, 0.f); p.gn = make_uint2(0u, 0u);
 #pragma unroll
@@ -149,10 +151,10 @@ __device__ inline void epi_unpark(const epi_pre *slot, epi_pre &p)
 
 // sum = the strip's accumulator (already summed over the K split)
 template <int NB, int EPI>
-__device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 sum, const epi_pre &p)
+__device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 sum, const epi_pre &p, int ct = 0)
 {
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
-    const int j = lane & 15, g = lane >> 4, rows = p.rows;
+    const int j = ct * 16 + (lane & 15), g = lane >> 4, rows = p.rows;
     float v[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) v[r] = (NB == 1) ? sum[r] + __shfl_down(sum[r], 8, 64) : sum[r];
@@ -197,7 +199,7 @@ __device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 
         }
     } else if (EPI == EPI_RESID) {
         v[0] += p.xo.x; v[1] += p.xo.y; v[2] += p.xo.z; v[3] += p.xo.w;       // xo is zero on dead lanes
-        emit_x<NB>(lane, rows, strip, a.d, v, p.gn, a.x, a.ssq_out, a.xop_out);
+        emit_x<NB>(lane, rows, strip, a.d, v, p.gn, a.x, a.ssq_out, a.xop_out, ct);
     } else if (EPI == EPI_SWIGLU) {
         float act[4];
 #pragma unroll

@@ -27,28 +27,30 @@
 
 struct mat_ws {                 // carved out of pv_ws::part
     uint16_t *xop_a, *xop_o, *xop_f, *xop_d;   // operands: QKV in (K=d), O in (K=qd), gate/up in (K=d), down in (K=F)
-    float *ssq0, *ssq1;                         // [d/16][16] partial sums of x^2
-    float *pmax_val; int32_t *pmax_idx;         // [16][vocab/16] per-strip arg-max candidates, row-major
+    float *ssq0, *ssq1;                         // [column tile][d/16][16] partial sums of x^2
+    float *pmax_val; int32_t *pmax_idx;         // [row][vocab/16] per-strip arg-max candidates, row-major
     float *attn_part;                           // attention chunk partials
 };
 
-static inline size_t xop_elems(int K) { return (size_t)2 * (K / 32) * 512; }   // hi and lo arrays
+static inline size_t xop_elems(int K) { return (size_t)2 * (K / 32) * 512; }   // hi and lo arrays of one 16-row column tile
+static inline int col_tiles(int rows) { return rows <= 16 ? 1 : rows <= 32 ? 2 : 4; }
 
 static size_t mat_ws_layout(const pv_model *m, int rows_cap, int max_tokens, float *base, mat_ws *w)
 {
     const pv_model_config &f = m->cfg;
     const int qd = f.n_q_heads * f.head_dim;
+    const size_t ctc = col_tiles(rows_cap);          // every per-row piece is sized for the widest block
     size_t off = 0;   // in floats, every piece a multiple of 64 floats (256 B)
     auto take = [&](size_t floats) { size_t o = off; off += (floats + 63) / 64 * 64; return base ? base + o : (float *)nullptr; };
     float *p;
-    p = take(xop_elems(f.d_model) / 2); if (w) w->xop_a = (uint16_t *)p;
-    p = take(xop_elems(qd) / 2); if (w) w->xop_o = (uint16_t *)p;
-    p = take(xop_elems(f.d_model) / 2); if (w) w->xop_f = (uint16_t *)p;
-    p = take(xop_elems(f.ffn_dim) / 2); if (w) w->xop_d = (uint16_t *)p;
-    p = take((size_t)f.d_model); if (w) w->ssq0 = p;
-    p = take((size_t)f.d_model); if (w) w->ssq1 = p;
-    p = take((size_t)f.vocab); if (w) w->pmax_val = p;
-    p = take((size_t)f.vocab); if (w) w->pmax_idx = (int32_t *)p;
+    p = take(ctc * xop_elems(f.d_model) / 2); if (w) w->xop_a = (uint16_t *)p;
+    p = take(ctc * xop_elems(qd) / 2); if (w) w->xop_o = (uint16_t *)p;
+    p = take(ctc * xop_elems(f.d_model) / 2); if (w) w->xop_f = (uint16_t *)p;
+    p = take(ctc * xop_elems(f.ffn_dim) / 2); if (w) w->xop_d = (uint16_t *)p;
+    p = take(ctc * (size_t)f.d_model); if (w) w->ssq0 = p;
+    p = take(ctc * (size_t)f.d_model); if (w) w->ssq1 = p;
+    p = take(ctc * (size_t)f.vocab); if (w) w->pmax_val = p;
+    p = take(ctc * (size_t)f.vocab); if (w) w->pmax_idx = (int32_t *)p;
     p = take(pv_attn_part_floats(m, rows_cap, max_tokens)); if (w) w->attn_part = p;
     return off;
 }
@@ -103,14 +105,15 @@ __global__ void __launch_bounds__(64)
 k_mat_begin(const pv_dev_state *st, const uint16_t *embed, const uint16_t *gain, const double *inv_freq,
             float *x, float *ssq, uint16_t *xop, float2 *rope, int d, int half)
 {
-    const int lane = threadIdx.x, j = lane & 15, g = lane >> 4, rows = st->gamma, strip = blockIdx.x;
+    const int lane = threadIdx.x, ct = blockIdx.y, j = ct * 16 + (lane & 15), g = lane >> 4, rows = st->gamma, strip = blockIdx.x;
     float v[4] = {0.f, 0.f, 0.f, 0.f};
     if (j < rows) {
         const uint16_t *e = embed + (size_t)st->draft[j] * d + strip * 16 + 4 * g;
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] = pv_bf16_to_f32(e[r]);
     }
-    emit_x<NB>(lane, rows, strip, d, v, *(const uint2 *)(gain + strip * 16 + 4 * g), x, ssq, xop);
+    emit_x<NB>(lane, rows, strip, d, v, *(const uint2 *)(gain + strip * 16 + 4 * g), x, ssq, xop, ct);
+    if (ct != 0) return;
     for (int idx = blockIdx.x * 64 + lane; idx < rows * half; idx += gridDim.x * 64) {
         const int jj = idx / half, i = idx - jj * half;
         double sn, cs;
@@ -132,102 +135,126 @@ __global__ void k_to_operand(const pv_dev_state *st, const float *src, uint16_t 
 }
 
 // ------------------------------------------------------------------------------------------
-// The streaming GEMM: one workgroup per strip, NW waves split K.
+// The streaming GEMM: one workgroup per strip, NW waves split K in batches of U tiles.
+//
+// Rows: NB == 1 packs up to 8 rows (hi and lo halves in one operand, CT == 1); NB == 2 takes the
+// rows in CT column tiles of 16, each with a hi and a lo operand, and keeps CT accumulators, so
+// one pass over the weights serves up to 16 * CT rows.
+//
+// K assignment: contiguous runs of batches per wave, or batch b to wave b % NW (the workgroup
+// then reads its strip as one advancing window).
 // ------------------------------------------------------------------------------------------
-template <int NB, int EPI, int NW>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NB == 1 ? 8 : 4)))   // <= 64 VGPRs: two 16-wave workgroups per CU
+template <int NB, int CT, int EPI, int NW>
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NB == 1 ? 8 : 4)))   // NB == 1: <= 64 VGPRs, two 16-wave workgroups per CU
 k_gemm(const gemm_args a)
 {
-    constexpr int U = 4;
+    static_assert(NB == 2 || CT == 1, "packed rows come in one tile");
+    constexpr int U = (CT >= 4) ? 2 : 4;
+    constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
     const int strip = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int KT = a.ktiles, nbat = KT / U;        // whole batches of U tiles; a ragged rest goes to the last wave
-    // K assignment: contiguous runs of batches per wave, or batch b to wave b % NW (the workgroup
-    // then reads its strip as one advancing window)
     int b, bend, bstep;
     if (a.interleave) { b = wave; bend = nbat; bstep = NW; }
     else { const int per = (nbat + NW - 1) / NW; b = min(nbat, wave * per); bend = min(nbat, b + per); bstep = 1; }
     const uint4 *A = a.W + (size_t)strip * KT * 64 + lane;
-    const uint4 *B = a.xop + lane;
-    const uint4 *B2 = a.xop + (size_t)KT * 64 + lane;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
+    const uint4 *B = a.xop + lane;                  // tile ct: hi at B + (2 ct) KT 64, lo at B + (2 ct + 1) KT 64   (NB == 2)
+    const size_t arr = (size_t)KT * 64;
+    f32x4 acc[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    __shared__ f32x4 red[NW][CT][64];
+    __shared__ float ssq_s[NW][CT][16];
+    __shared__ epi_pre pre_s[CT][64];
 
     // RMSNorm of the input rows: every wave takes its share of the per-strip sums of squares; the
-    // loads go out ahead of the weight stream and are folded in behind it
-    ssq_loads sl;
-    if (NORM) ssq_issue(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl);
-
-    // Few registers on purpose: latency is hidden by many resident workgroups per CU.
-    __shared__ f32x4 red[NW][64];
-    __shared__ float ssq_s[NW][16];
-    __shared__ epi_pre pre_s[64];
-    {   // first batch peeled: the sums of squares are folded in while its loads are in flight
-        uint4 ra[U], rb[U], rc[U];
-        const bool first = b < bend;
-        const int t = b * U;
-        if (first) {
+    // loads go out ahead of the weight stream and are folded in behind its first batch
+    ssq_loads sl[CT];
+    if (NORM) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                ra[u] = A[(size_t)(t + u) * 64]; rb[u] = B[(size_t)(t + u) * 64];
-                if (NB == 2) rc[u] = B2[(size_t)(t + u) * 64];
+        for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+    }
+
+    uint4 ra[U], rb[CT][U], rc[CT][U];
+    auto load_batch = [&](int t) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t o = (size_t)(t + u) * 64;
+            ra[u] = A[o];
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                rb[ct][u] = B[(size_t)(2 * ct) * arr + o];
+                if (NB == 2) rc[ct][u] = B[(size_t)(2 * ct + 1) * arr + o];
             }
         }
+    };
+    auto use_batch = [&]() {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                acc[ct] = mfma16(ra[u], rb[ct][u], acc[ct]);
+                if (NB == 2) acc[ct] = mfma16(ra[u], rc[ct][u], acc[ct]);
+            }
+    };
+
+    // Few registers on purpose (NB == 1): latency is hidden by many resident waves per CU.
+    {   // first batch peeled: the sums of squares are folded in while its loads are in flight
+        const bool first = b < bend;
+        if (first) load_batch(b * U);
         if (NORM) {
-            const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl);
-            if (lane < 4) *(float4 *)&ssq_s[wave][4 * lane] = s4;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                const float4 s4 = ssq_finish(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+                if (lane < 4) *(float4 *)&ssq_s[wave][ct][4 * lane] = s4;
+            }
         }
         if (wave == 0) {                            // behind the first batch's loads, ahead of its use
-            epi_pre pre;
-            epi_prefetch<EPI>(a, strip, lane, pre);
-            epi_park<EPI>(&pre_s[lane], pre);
-        }
-        if (first) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                acc = mfma16(ra[u], rb[u], acc);
-                if (NB == 2) acc = mfma16(ra[u], rc[u], acc);
+            for (int ct = 0; ct < CT; ++ct) {
+                epi_pre pre;
+                epi_prefetch<EPI>(a, strip, lane, pre, ct);
+                epi_park<EPI>(&pre_s[ct][lane], pre);
             }
-            b += bstep;
         }
+        if (first) { use_batch(); b += bstep; }
     }
     for (; b < bend; b += bstep) {
-        const int t = b * U;
-        uint4 ra[U], rb[U], rc[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            ra[u] = A[(size_t)(t + u) * 64]; rb[u] = B[(size_t)(t + u) * 64];
-            if (NB == 2) rc[u] = B2[(size_t)(t + u) * 64];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            acc = mfma16(ra[u], rb[u], acc);
-            if (NB == 2) acc = mfma16(ra[u], rc[u], acc);
-        }
+        load_batch(b * U);
+        use_batch();
     }
     if (wave == NW - 1) {
         for (int t = nbat * U; t < KT; ++t) {
-            const uint4 wa = A[(size_t)t * 64];
-            acc = mfma16(wa, B[(size_t)t * 64], acc);
-            if (NB == 2) acc = mfma16(wa, B2[(size_t)t * 64], acc);
+            const size_t o = (size_t)t * 64;
+            const uint4 wa = A[o];
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                acc[ct] = mfma16(wa, B[(size_t)(2 * ct) * arr + o], acc[ct]);
+                if (NB == 2) acc[ct] = mfma16(wa, B[(size_t)(2 * ct + 1) * arr + o], acc[ct]);
+            }
         }
     }
 
     // sum the NW K-slices (and the NW shares of the sums of squares) in wave order
-    red[wave][lane] = acc;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) red[wave][ct][lane] = acc[ct];
     __syncthreads();
     if (wave != 0) return;
-    f32x4 sum = red[0][lane];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) { const f32x4 p = red[w][lane]; sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3]; }
-    epi_pre pre;
-    epi_unpark<EPI>(&pre_s[lane], pre);
-    if (NORM) {
-        float tot = ssq_s[0][lane & 15];
+    for (int ct = 0; ct < CT; ++ct) {
+        f32x4 sum = red[0][ct][lane];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) tot += ssq_s[w][lane & 15];
-        pre.rj = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+        for (int w = 1; w < NW; ++w) { const f32x4 p = red[w][ct][lane]; sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3]; }
+        epi_pre pre;
+        epi_unpark<EPI>(&pre_s[ct][lane], pre);
+        if (NORM) {
+            float tot = ssq_s[0][ct][lane & 15];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) tot += ssq_s[w][ct][lane & 15];
+            pre.rj = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+        }
+        epi_apply<NB, EPI>(a, strip, lane, sum, pre, ct);
     }
-    epi_apply<NB, EPI>(a, strip, lane, sum, pre);
 }
 
 // arg-max over the per-strip candidates of one row
@@ -267,25 +294,29 @@ k_argmax_parts(pv_dev_state *st, const float *pv, const int32_t *pi, int strips)
 // strips, but no more than the K tiles can feed.
 static int g_tune_nw[4] = {0, 0, 0, 0};     // per epilogue kind; 0 = heuristic, else waves per workgroup
 
-template <int NB, int EPI>
+template <int NB, int CT, int EPI>
 static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStream_t s)
 {
     int nw = g_tune_nw[EPI];
     if (!nw) {
-        nw = g.ktiles >= 64 ? 16 : 8;                        // measured: 16-wave workgroups are never slower
+        nw = g.ktiles >= 64 ? 16 : 8;                        // measured: 16-wave workgroups are rarely slower
+        if (EPI == EPI_LMHEAD && g.ktiles <= 128) nw = 8;    // many strips of a short K: 8 waves measured faster
+        if (CT > 1) nw = 8;                                  // several accumulator tiles: registers and LDS for 8 waves
     }
     gemm_args ga = g;
     ga.interleave = g.ktiles > 128;                          // long strips: measured 0.3 % faster per step, short ones 0.3 % slower
-    switch (nw) {
-    case 4: k_gemm<NB, EPI, 4><<<strips, 256, 0, s>>>(ga); break;
-    case 16: k_gemm<NB, EPI, 16><<<strips, 1024, 0, s>>>(ga); break;
-    default: k_gemm<NB, EPI, 8><<<strips, 512, 0, s>>>(ga); break;
+    if constexpr (CT > 1) {
+        k_gemm<NB, CT, EPI, 8><<<strips, 512, 0, s>>>(ga);
+    } else {
+        if (nw == 8) k_gemm<NB, CT, EPI, 8><<<strips, 512, 0, s>>>(ga);
+        else if (nw == 4) k_gemm<NB, CT, EPI, 4><<<strips, 256, 0, s>>>(ga);
+        else k_gemm<NB, CT, EPI, 16><<<strips, 1024, 0, s>>>(ga);
     }
     PV_HIP(hipGetLastError());
     return PV_OK;
 }
 
-template <int NB>
+template <int NB, int CT>
 static int run_block(pv_cache *c, hipStream_t s)
 {
     const pv_model *m = c->m;
@@ -296,7 +327,7 @@ static int run_block(pv_cache *c, hipStream_t s)
     const char *Wb = m->d_weights;
     auto gainp = [&](int kind, int l) { return (const uint16_t *)(Wb + pv_tref(m, kind, l).off); };
 
-    k_mat_begin<NB><<<d / 16, 64, 0, s>>>(c->ws.state, (const uint16_t *)(Wb + m->global[PV_T_EMBED].off), gainp(PV_T_ATTN_NORM, 0),
+    k_mat_begin<NB><<<dim3(d / 16, CT), 64, 0, s>>>(c->ws.state, (const uint16_t *)(Wb + m->global[PV_T_EMBED].off), gainp(PV_T_ATTN_NORM, 0),
                                            (const double *)(Wb + m->inv_freq_off), c->ws.x, mw.ssq0, mw.xop_a, c->ws.rope, d, hd / 2);
     PV_HIP(hipGetLastError());
 
@@ -313,7 +344,7 @@ static int run_block(pv_cache *c, hipStream_t s)
         g.W = (const uint4 *)(Wb + pv_tref(m, PV_T_WQ, l).off); g.xop = (const uint4 *)mw.xop_a; g.ktiles = d / 32;
         g.ssq = mw.ssq0; g.layer = l;
         if ((prc = pv_prof_mark(c, PV_PROF_QKV, l, 0, s)) != PV_OK) return prc;
-        if ((prc = launch_gemm<NB, EPI_QKV>(m, g, (qd + 2 * kvd) / 16, s)) != PV_OK) return prc;
+        if ((prc = launch_gemm<NB, CT, EPI_QKV>(m, g, (qd + 2 * kvd) / 16, s)) != PV_OK) return prc;
         if ((prc = pv_prof_mark(c, PV_PROF_QKV, l, 1, s)) != PV_OK) return prc;
         // attention over the paged cache -> operand of the output projection
         if ((prc = pv_prof_mark(c, PV_PROF_ATTENTION, l, 0, s)) != PV_OK) return prc;
@@ -324,27 +355,27 @@ static int run_block(pv_cache *c, hipStream_t s)
         g.W = (const uint4 *)(Wb + pv_tref(m, PV_T_WO, l).off); g.xop = (const uint4 *)mw.xop_o; g.ktiles = qd / 32;
         g.gain_next = gainp(PV_T_FFN_NORM, l); g.ssq_out = mw.ssq1; g.xop_out = mw.xop_f;
         if ((prc = pv_prof_mark(c, PV_PROF_OPROJ, l, 0, s)) != PV_OK) return prc;
-        if ((prc = launch_gemm<NB, EPI_RESID>(m, g, d / 16, s)) != PV_OK) return prc;
+        if ((prc = launch_gemm<NB, CT, EPI_RESID>(m, g, d / 16, s)) != PV_OK) return prc;
         if ((prc = pv_prof_mark(c, PV_PROF_OPROJ, l, 1, s)) != PV_OK) return prc;
         // gate/up projection + SwiGLU
         g.W = (const uint4 *)(Wb + pv_tref(m, PV_T_WG, l).off); g.xop = (const uint4 *)mw.xop_f; g.ktiles = d / 32;
         g.ssq = mw.ssq1;
         if ((prc = pv_prof_mark(c, PV_PROF_GATEUP, l, 0, s)) != PV_OK) return prc;
-        if ((prc = launch_gemm<NB, EPI_SWIGLU>(m, g, F / 8, s)) != PV_OK) return prc;
+        if ((prc = launch_gemm<NB, CT, EPI_SWIGLU>(m, g, F / 8, s)) != PV_OK) return prc;
         if ((prc = pv_prof_mark(c, PV_PROF_GATEUP, l, 1, s)) != PV_OK) return prc;
         // down projection + residual; emits the next layer's (or the head's) operand
         g.W = (const uint4 *)(Wb + pv_tref(m, PV_T_WD, l).off); g.xop = (const uint4 *)mw.xop_d; g.ktiles = F / 32;
         g.gain_next = (l + 1 < f.n_layers) ? gainp(PV_T_ATTN_NORM, l + 1) : (const uint16_t *)(Wb + m->global[PV_T_FINAL_NORM].off);
         g.ssq_out = mw.ssq0; g.xop_out = mw.xop_a;
         if ((prc = pv_prof_mark(c, PV_PROF_DOWN, l, 0, s)) != PV_OK) return prc;
-        if ((prc = launch_gemm<NB, EPI_RESID>(m, g, d / 16, s)) != PV_OK) return prc;
+        if ((prc = launch_gemm<NB, CT, EPI_RESID>(m, g, d / 16, s)) != PV_OK) return prc;
         if ((prc = pv_prof_mark(c, PV_PROF_DOWN, l, 1, s)) != PV_OK) return prc;
     }
     const bool head = c->io->hdr[3] != PV_MODE_PREFILL_MID;
     if (head) {
         g.W = (const uint4 *)(Wb + m->global[PV_T_LM_HEAD].off); g.xop = (const uint4 *)mw.xop_a; g.ktiles = d / 32; g.ssq = mw.ssq0;
         if ((prc = pv_prof_mark(c, PV_PROF_LMHEAD, 0, 0, s)) != PV_OK) return prc;
-        if ((prc = launch_gemm<NB, EPI_LMHEAD>(m, g, f.vocab / 16, s)) != PV_OK) return prc;
+        if ((prc = launch_gemm<NB, CT, EPI_LMHEAD>(m, g, f.vocab / 16, s)) != PV_OK) return prc;
         if ((prc = pv_prof_mark(c, PV_PROF_LMHEAD, 0, 1, s)) != PV_OK) return prc;
         k_argmax_parts<<<rows, 256, 0, s>>>(c->ws.state, mw.pmax_val, mw.pmax_idx, f.vocab / 16);
         PV_HIP(hipGetLastError());
@@ -354,6 +385,10 @@ static int run_block(pv_cache *c, hipStream_t s)
 
 int pv_mat_run_block(pv_cache *c, hipStream_t s)
 {
-    if (c->last_rows > 16) { pv_set_error("matrix path handles at most 16 rows per block"); return PV_ERANGE; }
-    return c->last_rows <= 8 ? run_block<1>(c, s) : run_block<2>(c, s);
+    const int rows = c->last_rows;
+    if (rows > 64) { pv_set_error("matrix path handles at most 64 rows per block"); return PV_ERANGE; }
+    if (rows <= 8) return run_block<1, 1>(c, s);
+    if (rows <= 16) return run_block<2, 1>(c, s);
+    if (rows <= 32) return run_block<2, 2>(c, s);
+    return run_block<2, 4>(c, s);
 }

@@ -14,8 +14,9 @@ __device__ inline f32x4 mfma16(uint4 a, uint4 b, f32x4 c)
 
 // ------------------------------------------------------------------------------------------
 // Operand writers.  Element (row j, K-index k) of an activation lives at
-//   arr[(k/32)*512 + (col + 16*((k%32)/8))*8 + k%8],  col = j (hi) / j+8 (lo) when NB == 1,
-//   and col = j in the hi array / lo array when NB == 2.
+//   arr[(k/32)*512 + (col + 16*((k%32)/8))*8 + k%8],  col = j (hi) / j+8 (lo) when NB == 1
+//   (at most 8 rows).  When NB == 2 the rows come in column tiles of 16: tile j/16 owns a hi
+//   array followed by a lo array ((K/32)*512 elements each), col = j%16 in both.
 // ------------------------------------------------------------------------------------------
 __device__ inline uint16_t bf16_rne(float f) { return pv_f32_to_bf16(f); }
 
@@ -33,8 +34,10 @@ __device__ inline void store_operand4(uint16_t *xop, int K, int j, int k0, const
         *(uint2 *)(xop + tile + in + (size_t)j * 8) = vh;
         *(uint2 *)(xop + tile + in + (size_t)(j + 8) * 8) = vl;
     } else {
-        *(uint2 *)(xop + tile + in + (size_t)j * 8) = vh;
-        *(uint2 *)(xop + (size_t)(K / 32) * 512 + tile + in + (size_t)j * 8) = vl;
+        const size_t arr = (size_t)(K / 32) * 512;
+        uint16_t *base = xop + (size_t)(j >> 4) * 2 * arr + tile + in + (size_t)(j & 15) * 8;
+        *(uint2 *)base = vh;
+        *(uint2 *)(base + arr) = vl;
     }
 }
 

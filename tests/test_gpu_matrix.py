@@ -38,19 +38,18 @@ def _rel_err(pvlib, lg_g, lg_r):
 CASES = [(MAT_A, 0), (MAT_B, 0), (MAT_C, 0), (FUSE_A, 0), (FUSE_B, 2)]
 
 
-@pytest.mark.parametrize("shape,path", CASES, ids=lambda v: v.name if hasattr(v, "name") else f"path{v}")
-def test_matrix_path_matches_oracle(pvlib, shape, path):
+def _check_against_oracle(pvlib, shape, path, max_gamma, prompt_len, gammas, cache_tokens):
     from gpu_helpers import gpu_model, top2_margin
-    gm = gpu_model(shape, gains="perturbed", kernel_path=path)
+    gm = gpu_model(shape, gains="perturbed", kernel_path=path, max_gamma=max_gamma)
     rm = ref_model(shape, gains="perturbed")
-    prompt = pv_inputs.uniform_tokens(61, 37, shape.vocab)
-    gc, rc = pvlib.Cache(gm, 96), ref.RefCache(rm, 96, ref.KV_BF16)
-    gc.prefill(prompt)                      # chunks of 16, 16, 5 rows
+    prompt = pv_inputs.uniform_tokens(61, prompt_len, shape.vocab)
+    gc, rc = pvlib.Cache(gm, cache_tokens), ref.RefCache(rm, cache_tokens, ref.KV_BF16)
+    gc.prefill(prompt)                      # chunks of max_gamma rows and a ragged last one
     last = rc.prefill(prompt)
     assert _rel_err(pvlib, gc.debug_logits()[-1:], last[None]) < 2e-3
-    assert gc.state() == (37, rc.pending)
+    assert gc.state() == (prompt_len, rc.pending)
     worst = 0.0
-    for step, gamma in enumerate((8, 13, 1, 5, 16, 3)):
+    for step, gamma in enumerate(gammas):
         T = len(rc)
         d = pv_inputs.uniform_tokens(62 + step, gamma, shape.vocab)
         d[0] = rc.pending
@@ -72,6 +71,18 @@ def test_matrix_path_matches_oracle(pvlib, shape, path):
     print(f"{shape.name}: worst rel logit err {worst:.2e}, KV 1-ulp flips {np.mean(ge != re_):.4f}")
     assert ge.shape == re_.shape and np.mean(ge != re_) < 0.05     # 1-ulp bf16 flips at rounding boundaries only
     assert np.abs(ge - re_).max() <= 2.0 ** -7 * np.abs(re_).max()
+
+
+@pytest.mark.parametrize("shape,path", CASES, ids=lambda v: v.name if hasattr(v, "name") else f"path{v}")
+def test_matrix_path_matches_oracle(pvlib, shape, path):
+    _check_against_oracle(pvlib, shape, path, 16, 37, (8, 13, 1, 5, 16, 3), 96)   # prefill chunks of 16, 16, 5 rows
+
+
+@pytest.mark.parametrize("shape", [MAT_A, MAT_C, FUSE_A], ids=lambda v: v.name)
+def test_wide_blocks_match_oracle(pvlib, shape):
+    """Blocks of 17..64 rows (two and four 16-row column tiles per weight pass), next to narrow
+    ones on the same cache; the prompt is prefilled in 64-row chunks plus a ragged rest."""
+    _check_against_oracle(pvlib, shape, 0, 64, 100, (32, 17, 64, 8, 40, 1, 33), 320)
 
 
 def test_matrix_and_vector_paths_agree(pvlib):
