@@ -135,37 +135,48 @@ __global__ void k_to_operand(const pv_dev_state *st, const float *src, uint16_t 
 }
 
 // ------------------------------------------------------------------------------------------
-// The streaming GEMM: one workgroup per strip, NW waves split K in batches of U tiles.
+// The streaming GEMM: a workgroup owns S adjacent strips, its NW waves split K in batches of U
+// tiles.
 //
-// Rows: NB == 1 packs up to 8 rows (hi and lo halves in one operand, CT == 1); NB == 2 takes the
-// rows in CT column tiles of 16, each with a hi and a lo operand, and keeps CT accumulators, so
-// one pass over the weights serves up to 16 * CT rows.
+// Rows: NB == 1 packs up to 8 rows (hi and lo halves in one operand; CT == 1, S == 1).  NB == 2
+// takes the rows in CT column tiles of 16, each with a hi and a lo operand, and keeps S x CT
+// accumulators: every operand tile fetched from L2 is used for S strips from registers, which
+// keeps the operand traffic (2 CT tiles per batch tile) from outgrowing the weight stream
+// (S tiles) in the CU's load path.
 //
 // K assignment: contiguous runs of batches per wave, or batch b to wave b % NW (the workgroup
-// then reads its strip as one advancing window).
+// then reads its strips as advancing windows).
 // ------------------------------------------------------------------------------------------
-template <int NB, int CT, int EPI, int NW>
+template <int NB, int CT, int S, int EPI, int NW>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NB == 1 ? 8 : 4)))   // NB == 1: <= 64 VGPRs, two 16-wave workgroups per CU
 k_gemm(const gemm_args a)
 {
-    static_assert(NB == 2 || CT == 1, "packed rows come in one tile");
-    constexpr int U = (CT >= 4) ? 2 : 4;
+    static_assert(NB == 2 || (CT == 1 && S == 1), "packed rows: one tile, one strip");
+    static_assert(S <= NW, "one epilogue wave per strip");
+    constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : 4;
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
-    const int strip = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    constexpr bool PARK = (S == 1 && CT == 1);       // epilogue inputs fetched early and parked in LDS
+    const int strip0 = blockIdx.x * S, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int KT = a.ktiles, nbat = KT / U;        // whole batches of U tiles; a ragged rest goes to the last wave
     int b, bend, bstep;
     if (a.interleave) { b = wave; bend = nbat; bstep = NW; }
     else { const int per = (nbat + NW - 1) / NW; b = min(nbat, wave * per); bend = min(nbat, b + per); bstep = 1; }
-    const uint4 *A = a.W + (size_t)strip * KT * 64 + lane;
-    const uint4 *B = a.xop + lane;                  // tile ct: hi at B + (2 ct) KT 64, lo at B + (2 ct + 1) KT 64   (NB == 2)
-    const size_t arr = (size_t)KT * 64;
-    f32x4 acc[CT];
+    const size_t arr = (size_t)KT * 64;             // tiles of one strip = elements of one operand array, in uint4
+    const uint4 *A = a.W + (size_t)strip0 * arr + lane;
+    const uint4 *B = a.xop + lane;                  // tile ct: hi at B + (2 ct) arr, lo at B + (2 ct + 1) arr   (NB == 2)
+    // a ragged last workgroup re-reads its first strip for the missing ones and drops the result
+    size_t so[S];
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) acc[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int si = 0; si < S; ++si) so[si] = (strip0 + si < a.nstrips) ? (size_t)si * arr : 0;
+    f32x4 acc[S][CT];
+#pragma unroll
+    for (int si = 0; si < S; ++si)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) acc[si][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    __shared__ f32x4 red[NW][CT][64];
+    __shared__ f32x4 red[NW][S][CT][64];
     __shared__ float ssq_s[NW][CT][16];
-    __shared__ epi_pre pre_s[CT][64];
+    __shared__ epi_pre pre_s[PARK ? 64 : 1];
 
     // RMSNorm of the input rows: every wave takes its share of the per-strip sums of squares; the
     // loads go out ahead of the weight stream and are folded in behind its first batch
@@ -175,12 +186,13 @@ k_gemm(const gemm_args a)
         for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
     }
 
-    uint4 ra[U], rb[CT][U], rc[CT][U];
+    uint4 ra[S][U], rb[CT][U], rc[CT][U];
     auto load_batch = [&](int t) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const size_t o = (size_t)(t + u) * 64;
-            ra[u] = A[o];
+#pragma unroll
+            for (int si = 0; si < S; ++si) ra[si][u] = A[so[si] + o];
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 rb[ct][u] = B[(size_t)(2 * ct) * arr + o];
@@ -192,10 +204,12 @@ k_gemm(const gemm_args a)
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                acc[ct] = mfma16(ra[u], rb[ct][u], acc[ct]);
-                if (NB == 2) acc[ct] = mfma16(ra[u], rc[ct][u], acc[ct]);
-            }
+            for (int si = 0; si < S; ++si)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    acc[si][ct] = mfma16(ra[si][u], rb[ct][u], acc[si][ct]);
+                    if (NB == 2) acc[si][ct] = mfma16(ra[si][u], rc[ct][u], acc[si][ct]);
+                }
     };
 
     // Few registers on purpose (NB == 1): latency is hidden by many resident waves per CU.
@@ -209,13 +223,10 @@ k_gemm(const gemm_args a)
                 if (lane < 4) *(float4 *)&ssq_s[wave][ct][4 * lane] = s4;
             }
         }
-        if (wave == 0) {                            // behind the first batch's loads, ahead of its use
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                epi_pre pre;
-                epi_prefetch<EPI>(a, strip, lane, pre, ct);
-                epi_park<EPI>(&pre_s[ct][lane], pre);
-            }
+        if (PARK && wave == 0) {                    // behind the first batch's loads, ahead of its use
+            epi_pre pre;
+            epi_prefetch<EPI>(a, strip0, lane, pre, 0);
+            epi_park<EPI>(&pre_s[lane], pre);
         }
         if (first) { use_batch(); b += bstep; }
     }
@@ -226,27 +237,37 @@ k_gemm(const gemm_args a)
     if (wave == NW - 1) {
         for (int t = nbat * U; t < KT; ++t) {
             const size_t o = (size_t)t * 64;
-            const uint4 wa = A[o];
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
-                acc[ct] = mfma16(wa, B[(size_t)(2 * ct) * arr + o], acc[ct]);
-                if (NB == 2) acc[ct] = mfma16(wa, B[(size_t)(2 * ct + 1) * arr + o], acc[ct]);
+                const uint4 bh = B[(size_t)(2 * ct) * arr + o];
+                uint4 bl = bh;
+                if (NB == 2) bl = B[(size_t)(2 * ct + 1) * arr + o];
+#pragma unroll
+                for (int si = 0; si < S; ++si) {
+                    const uint4 wa = A[so[si] + o];
+                    acc[si][ct] = mfma16(wa, bh, acc[si][ct]);
+                    if (NB == 2) acc[si][ct] = mfma16(wa, bl, acc[si][ct]);
+                }
             }
         }
     }
 
-    // sum the NW K-slices (and the NW shares of the sums of squares) in wave order
+    // sum the NW K-slices (and the NW shares of the sums of squares) in wave order; wave si runs
+    // the epilogue of strip strip0 + si
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) red[wave][ct][lane] = acc[ct];
+    for (int si = 0; si < S; ++si)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) red[wave][si][ct][lane] = acc[si][ct];
     __syncthreads();
-    if (wave != 0) return;
+    if (wave >= S || strip0 + wave >= a.nstrips) return;
+    const int strip = strip0 + wave;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
-        f32x4 sum = red[0][ct][lane];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) { const f32x4 p = red[w][ct][lane]; sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3]; }
+        f32x4 sum = red[0][wave][ct][lane];
+        for (int w = 1; w < NW; ++w) { const f32x4 p = red[w][wave][ct][lane]; sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3]; }
         epi_pre pre;
-        epi_unpark<EPI>(&pre_s[ct][lane], pre);
+        if (PARK) epi_unpark<EPI>(&pre_s[lane], pre);
+        else epi_prefetch<EPI>(a, strip, lane, pre, ct);
         if (NORM) {
             float tot = ssq_s[0][ct][lane & 15];
 #pragma unroll
@@ -297,20 +318,26 @@ static int g_tune_nw[4] = {0, 0, 0, 0};     // per epilogue kind; 0 = heuristic,
 template <int NB, int CT, int EPI>
 static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStream_t s)
 {
-    int nw = g_tune_nw[EPI];
-    if (!nw) {
-        nw = g.ktiles >= 64 ? 16 : 8;                        // measured: 16-wave workgroups are rarely slower
-        if (EPI == EPI_LMHEAD && g.ktiles <= 128) nw = 8;    // many strips of a short K: 8 waves measured faster
-        if (CT > 1) nw = 8;                                  // several accumulator tiles: registers and LDS for 8 waves
-    }
     gemm_args ga = g;
+    ga.nstrips = strips;
     ga.interleave = g.ktiles > 128;                          // long strips: measured 0.3 % faster per step, short ones 0.3 % slower
-    if constexpr (CT > 1) {
-        k_gemm<NB, CT, EPI, 8><<<strips, 512, 0, s>>>(ga);
+    if constexpr (NB == 2) {
+        // Strips per workgroup: with enough strips to fill the machine anyway, the 2 CT operand
+        // tiles per batch tile are matched by as many weight tiles (S = 2 or 4); a GEMM with few
+        // strips keeps one strip per workgroup and more waves instead.
+        constexpr int S = CT == 1 ? 2 : 4, NW = CT == 1 ? 8 : 4;
+        if (strips >= 256 * S) k_gemm<NB, CT, S, EPI, NW><<<(strips + S - 1) / S, NW * 64, 0, s>>>(ga);
+        else if (CT == 1 && g.ktiles >= 64) k_gemm<NB, CT, 1, EPI, 16><<<strips, 1024, 0, s>>>(ga);
+        else k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
     } else {
-        if (nw == 8) k_gemm<NB, CT, EPI, 8><<<strips, 512, 0, s>>>(ga);
-        else if (nw == 4) k_gemm<NB, CT, EPI, 4><<<strips, 256, 0, s>>>(ga);
-        else k_gemm<NB, CT, EPI, 16><<<strips, 1024, 0, s>>>(ga);
+        int nw = g_tune_nw[EPI];
+        if (!nw) {
+            nw = g.ktiles >= 64 ? 16 : 8;                        // measured: 16-wave workgroups are rarely slower
+            if (EPI == EPI_LMHEAD && g.ktiles <= 128) nw = 8;    // many strips of a short K: 8 waves measured faster
+        }
+        if (nw == 8) k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
+        else if (nw == 4) k_gemm<NB, CT, 1, EPI, 4><<<strips, 256, 0, s>>>(ga);
+        else k_gemm<NB, CT, 1, EPI, 16><<<strips, 1024, 0, s>>>(ga);
     }
     PV_HIP(hipGetLastError());
     return PV_OK;
