@@ -113,6 +113,7 @@ def main():
     ap.add_argument("--prefix", type=int, default=None)
     ap.add_argument("--alpha", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graphs", action="store_true", help="plain launches instead of HIP-graph replay of the step (comparison runs)")
     ap.add_argument("--prof-kernel", default="gateup")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
                     help="also launch the library's plain copy kernel on this many MiB three times (the known "
@@ -140,7 +141,7 @@ def main():
     model = load_model(pv, pv_inputs, shape, max_gamma=16 if gamma <= 16 else 64)
     max_tokens = T0 + (2 * n_steps + 2) * gamma + 16
     cache = pv.Cache(model, max_tokens)
-    if os.environ.get("PV_BENCH_GRAPHS") == "0":     # comparison runs: plain launches instead of graph replay
+    if a.no_graphs:
         cache.use_graphs(False)
     prompt = pv_inputs.uniform_tokens(2000 + shape.seed, T0, shape.vocab)
     t0 = time.time()

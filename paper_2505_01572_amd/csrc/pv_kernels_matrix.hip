@@ -122,18 +122,6 @@ k_mat_begin(const pv_dev_state *st, const uint16_t *embed, const uint16_t *gain,
     }
 }
 
-// fp32 [rows][K] -> operand (no gain); used for the attention output
-template <int NB>
-__global__ void k_to_operand(const pv_dev_state *st, const float *src, uint16_t *xop, int K)
-{
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;       // (row, group of 4)
-    const int per_row = K / 4, j = idx / per_row, k0 = (idx - j * per_row) * 4;
-    if (j >= st->gamma) return;
-    const float4 a = *(const float4 *)(src + (size_t)j * K + k0);
-    const float y[4] = {a.x, a.y, a.z, a.w};
-    store_operand4<NB>(xop, K, j, k0, y);
-}
-
 // ------------------------------------------------------------------------------------------
 // The streaming GEMM: a workgroup owns S adjacent strips, its NW waves split K in batches of U
 // tiles.
@@ -311,9 +299,6 @@ k_argmax_parts(pv_dev_state *st, const float *pv, const int32_t *pi, int strips)
 // ------------------------------- host side ----------------------------------------
 
 
-// Waves per workgroup (= K split): enough waves to fill the machine even when there are few
-// strips, but no more than the K tiles can feed.
-static int g_tune_nw[4] = {0, 0, 0, 0};     // per epilogue kind; 0 = heuristic, else waves per workgroup
 
 template <int NB, int CT, int EPI>
 static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStream_t s)
@@ -330,13 +315,10 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         else if (CT == 1 && g.ktiles >= 64) k_gemm<NB, CT, 1, EPI, 16><<<strips, 1024, 0, s>>>(ga);
         else k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
     } else {
-        int nw = g_tune_nw[EPI];
-        if (!nw) {
-            nw = g.ktiles >= 64 ? 16 : 8;                        // measured: 16-wave workgroups are rarely slower
-            if (EPI == EPI_LMHEAD && g.ktiles <= 128) nw = 8;    // many strips of a short K: 8 waves measured faster
-        }
-        if (nw == 8) k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
-        else if (nw == 4) k_gemm<NB, CT, 1, EPI, 4><<<strips, 256, 0, s>>>(ga);
+        // waves per workgroup (= K split): 16 where K can feed them (measured rarely slower), 8 for
+        // a short K and for the many strips of a short-K vocabulary projection (measured faster)
+        const bool eight = g.ktiles < 64 || (EPI == EPI_LMHEAD && g.ktiles <= 128);
+        if (eight) k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
         else k_gemm<NB, CT, 1, EPI, 16><<<strips, 1024, 0, s>>>(ga);
     }
     PV_HIP(hipGetLastError());
