@@ -96,6 +96,22 @@ def silu(z, real="f64"):
     return load(real).ref_silu(z)
 
 
+def dequant_q4(codes, scales):
+    """Weights of a 4-bit matrix as float32 (exact): w[r, k] = (code[r, k] - 8) * scale[r, k // 32].
+    codes: uint8 [rows, cols/2], two codes per byte, the even input feature in the low nibble;
+    scales: bf16 bit patterns [rows, cols/32].  (The paper runs its 70B model in 4 bit, Sec. 4.1,
+    without naming a format; this is the group-wise symmetric one the build settled on.)"""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    rows, half = codes.shape
+    c = np.empty((rows, 2 * half), dtype=np.int32)
+    c[:, 0::2] = codes & 15
+    c[:, 1::2] = codes >> 4
+    s = (np.ascontiguousarray(scales, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    assert s.shape == (rows, 2 * half // 32)
+    w = (c - 8).astype(np.float32).reshape(rows, -1, 32) * s[:, :, None]
+    return np.ascontiguousarray(w.reshape(rows, 2 * half))
+
+
 class RefModel:
     def __init__(self, shape, real="f64"):
         """shape: any object with n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab,

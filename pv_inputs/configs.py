@@ -30,6 +30,7 @@ class ModelShape:
     dtype: str = "bf16"          # storage type of weights and KV cache: "f32" | "bf16"
     page_tokens: int = 16
     seed: int = 1000
+    weight_bits: int = 16        # 16: matrices stored in `dtype`; 4: projection matrices and LM head as 4-bit codes + bf16 group scales
 
     def replace(self, **kw):
         d = asdict(self)
@@ -51,6 +52,11 @@ class ModelShape:
     def streamed_bytes(self):
         """Bytes of weights one verify step must read: everything except the embedding table."""
         eb = 2 if self.dtype == "bf16" else 4
+        if self.weight_bits == 4:
+            mats = sum(_numel(tensor_shape(self, k)) for k in PER_LAYER if len(tensor_shape(self, k)) == 2) * self.n_layers
+            mats += _numel(tensor_shape(self, "lm_head"))
+            gains = self.n_params() - _numel(tensor_shape(self, "embed")) - mats
+            return mats * 9 // 16 + gains * eb           # 4 bits + one bf16 scale per 32 weights = 4.5 bits
         return (self.n_params() - _numel(tensor_shape(self, "embed"))) * eb
 
     def kv_bytes_per_token(self):
@@ -89,4 +95,7 @@ CONFIGS = {
     "1b": ModelShape("1b", 16, 2048, 32, 8, 64, 8192, 128256, rope_base=500000.0, seed=1004),
     "70b_v128k": ModelShape("70b_v128k", 80, 8192, 64, 8, 128, 28672, 128256,
                             rope_base=500000.0, seed=1005),
+    # 4-bit variants of the verifier shapes (the paper runs its 70B model in 4 bit, Sec. 4.1)
+    "70b_q4": ModelShape("70b_q4", 80, 8192, 64, 8, 128, 28672, 32000, seed=1003, weight_bits=4),
+    "8b_q4": ModelShape("8b_q4", 32, 4096, 32, 8, 128, 14336, 128256, rope_base=500000.0, seed=1002, weight_bits=4),
 }

@@ -77,3 +77,46 @@ int pvs_fill_unit(uint64_t seed, uint64_t stream, uint64_t start, uint64_t count
         out[j] = (double)(pvs_draw(key, start + j) >> 11) * (1.0 / 9007199254740992.0);
     return 0;
 }
+
+/* ---- 4-bit weight format (input preparation: the stand-in for a 4-bit checkpoint) ----
+ *
+ * A matrix row is cut into groups of 32 consecutive input features.  Each group carries one
+ * bf16 scale s = bf16(max|w| / 7) (s = bf16(2^-126-ish floor) replaced by 1.0 for an all-zero
+ * group) and 32 codes c = clamp(rint(w / s) + 8, 0, 15); the weight the model uses is
+ * (c - 8) * s.  Codes are packed two per byte, the even feature in the low nibble.
+ * w: bf16 bit patterns [rows][cols], cols % 32 == 0.  Arithmetic in float, round-half-even.
+ */
+#include <math.h>
+
+static inline float pvs_bf16_to_f32(uint16_t b) { uint32_t u = (uint32_t)b << 16; float f; memcpy(&f, &u, 4); return f; }
+static inline uint16_t pvs_f32_to_bf16(float f)
+{
+    uint32_t u; memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+int pvs_quantize_q4(const uint16_t *w, int64_t rows, int64_t cols, uint8_t *codes, uint16_t *scales)
+{
+    if (cols % 32) return -1;
+    const int64_t groups = cols / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t g = 0; g < groups; ++g) {
+            const uint16_t *src = w + r * cols + g * 32;
+            float v[32], m = 0.f;
+            for (int k = 0; k < 32; ++k) { v[k] = pvs_bf16_to_f32(src[k]); const float a = fabsf(v[k]); if (a > m) m = a; }
+            uint16_t sb = pvs_f32_to_bf16(m / 7.0f);
+            float s = pvs_bf16_to_f32(sb);
+            if (!(s > 0.f)) { sb = 0x3F80; s = 1.0f; }
+            scales[r * groups + g] = sb;
+            uint8_t *dst = codes + r * (cols / 2) + g * 16;
+            for (int k = 0; k < 32; k += 2) {
+                int c0 = (int)rintf(v[k] / s) + 8, c1 = (int)rintf(v[k + 1] / s) + 8;
+                c0 = c0 < 0 ? 0 : c0 > 15 ? 15 : c0; c1 = c1 < 0 ? 0 : c1 > 15 ? 15 : c1;
+                dst[k / 2] = (uint8_t)(c0 | (c1 << 4));
+            }
+        }
+    }
+    return 0;
+}

@@ -39,6 +39,8 @@ def _load():
         u64, vp = ctypes.c_uint64, ctypes.c_void_p
         lib.pvs_fill_table.argtypes = [u64, u64, u64, u64, vp, ctypes.c_int, vp]
         lib.pvs_fill_table.restype = ctypes.c_int
+        lib.pvs_quantize_q4.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, vp, vp]
+        lib.pvs_quantize_q4.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -169,3 +171,47 @@ def iter_row_chunks(m: ModelShape, kind: str, layer: int, max_rows: int, gains: 
         n = min(max_rows, rows - r0)
         buf = None if (scratch is None or is_gain) else scratch
         yield r0, fill_tensor(m, kind, layer, start=r0 * cols, count=n * cols, gains=gains, out=buf).reshape(n, cols)
+
+
+# ---- 4-bit weight format: input preparation (the stand-in for a 4-bit checkpoint) ----
+
+Q4_GROUP = 32
+
+
+def quantize_q4(w_bits, use_native=True):
+    """bf16 bit patterns [rows, cols] (cols % 32 == 0) -> (codes uint8 [rows, cols/2], scales
+    uint16 = bf16 bits [rows, cols/32]).  Per group of 32 input features: scale = bf16(max|w| / 7)
+    (1.0 for an all-zero group), code = clamp(rint(w / scale) + 8, 0, 15), two codes per byte with
+    the even feature in the low nibble.  The weight a 4-bit model uses is (code - 8) * scale."""
+    w_bits = np.ascontiguousarray(w_bits, dtype=np.uint16)
+    rows, cols = w_bits.shape
+    assert cols % Q4_GROUP == 0
+    lib = _load() if use_native else None
+    codes = np.empty((rows, cols // 2), dtype=np.uint8)
+    scales = np.empty((rows, cols // Q4_GROUP), dtype=np.uint16)
+    if lib is not None:
+        rc = lib.pvs_quantize_q4(w_bits.ctypes.data, rows, cols, codes.ctypes.data, scales.ctypes.data)
+        assert rc == 0
+        return codes, scales
+    v = bf16_bits_to_f32(w_bits).reshape(rows, cols // Q4_GROUP, Q4_GROUP)
+    m = np.abs(v).max(axis=2)
+    sbits = bf16_round_f32((m / np.float32(7.0)).astype(np.float32))
+    sb = bf16_bits_to_f32(sbits)
+    dead = ~(sb > 0)
+    sbits = np.where(dead, np.uint16(0x3F80), sbits).astype(np.uint16)
+    sb = np.where(dead, np.float32(1.0), sb).astype(np.float32)
+    c = np.clip(np.rint(v / sb[:, :, None]).astype(np.int32) + 8, 0, 15).astype(np.uint8).reshape(rows, cols)
+    codes[:] = c[:, 0::2] | (c[:, 1::2] << 4)
+    scales[:] = sbits
+    return codes, scales
+
+
+Q4_KINDS = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "lm_head")      # matrices a 4-bit model stores as codes + scales
+
+
+def iter_row_chunks_q4(m: ModelShape, kind: str, layer: int, max_rows: int, scratch=None):
+    """Like iter_row_chunks for a matrix of a 4-bit model: yields (row_begin, codes, scales)."""
+    assert kind in Q4_KINDS
+    for r0, rows in iter_row_chunks(m, kind, layer, max_rows, scratch=scratch):
+        codes, scales = quantize_q4(rows)
+        yield r0, codes, scales

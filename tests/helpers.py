@@ -13,6 +13,9 @@ def ref_model(shape, gains="ones", real="f64", overrides=None):
         arr = arr.reshape(pv_inputs.tensor_shape(shape, kind))
         if overrides and (kind, layer) in overrides:
             arr = overrides[(kind, layer)]
+        elif getattr(shape, "weight_bits", 16) == 4 and kind in pv_inputs.Q4_KINDS:
+            codes, scales = pv_inputs.quantize_q4(arr)          # the model's weights ARE the codes and scales
+            arr = ref.dequant_q4(codes, scales)
         m.set_tensor(kind, layer, arr)
     return m
 

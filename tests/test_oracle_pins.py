@@ -306,3 +306,62 @@ def ref_clone(m, prompt_len, max_tokens):
     c = ref.RefCache(m, max_tokens)
     c.prefill(pv_inputs.uniform_tokens(21, prompt_len, TINY.vocab))
     return c
+
+
+# ---- 4-bit weights: the dequantisation rule and the input-side quantiser ----
+
+def test_q4_dequant_closed_forms_and_nibble_order():
+    # one row, two groups; scale bits 0x3F00 = 0.5 and 0x4000 = 2.0
+    codes = np.zeros((1, 32), dtype=np.uint8)
+    k = np.arange(64)
+    c = (k * 7 + 3) % 16                                   # every code value occurs
+    codes[0] = (c[0::2] | (c[1::2] << 4)).astype(np.uint8)  # even feature in the low nibble
+    scales = np.array([[0x3F00, 0x4000]], dtype=np.uint16)
+    w = ref.dequant_q4(codes, scales)
+    expect = (c - 8) * np.where(k < 32, 0.5, 2.0)
+    assert w.dtype == np.float32 and np.array_equal(w[0], expect.astype(np.float32))
+    assert w[0][c == 8].tolist() == [0.0] * int((c == 8).sum())      # code 8 is zero whatever the scale
+    assert w[0].min() == -8 * 2.0 and w[0].max() == 7 * 2.0
+
+
+def test_q4_quantiser_roundtrip_properties():
+    rng = np.random.default_rng(5)
+    w = (rng.standard_normal((48, 256)) * 0.02).astype(np.float32)
+    bits = pv_inputs.bf16_round_f32(w)
+    bits[7, 64:96] = 0                                     # an all-zero group
+    wf = pv_inputs.bf16_bits_to_f32(bits)
+    codes, scales = pv_inputs.quantize_q4(bits)
+    c2, s2 = pv_inputs.quantize_q4(bits, use_native=False)  # the C routine and its numpy twin agree
+    assert np.array_equal(codes, c2) and np.array_equal(scales, s2)
+    dq = ref.dequant_q4(codes, scales)
+    s = pv_inputs.bf16_bits_to_f32(scales)
+    # error at most half a step, except where +max clips to code 15 = 7 steps (max / 7 rounded down to bf16)
+    err = np.abs(dq - wf).reshape(48, 8, 32)
+    assert (err <= 0.5 * s[:, :, None] * (1 + 2.0 ** -7) + np.abs(wf).reshape(48, 8, 32) * 2.0 ** -7).all()
+    assert np.array_equal(dq[7, 64:96], np.zeros(32, dtype=np.float32)) and scales[7, 2] == 0x3F80
+    # weights that are integer multiples of a bf16 step survive exactly
+    step = np.float32(0.015625)
+    ints = rng.integers(-7, 8, size=(4, 64)); ints[:, 0] = 7; ints[:, 32] = -7
+    exact = (ints * step).astype(np.float32)
+    codes, scales = pv_inputs.quantize_q4(pv_inputs.bf16_round_f32(exact))
+    assert np.array_equal(ref.dequant_q4(codes, scales), exact)
+
+
+def test_q4_linear_equals_integer_arithmetic():
+    """A projection with 4-bit weights, by brute force in exact integer arithmetic: with small
+    integer activations, y[n] = sum_g scale[n, g] * sum_{k in g} (code - 8) * x[k]."""
+    rng = np.random.default_rng(6)
+    N, K = 16, 96
+    c = rng.integers(0, 16, size=(N, K))
+    codes = (c[:, 0::2] | (c[:, 1::2] << 4)).astype(np.uint8)
+    sc = np.array([0.25, 1.0, 8.0, 0.5, 2.0, 0.125])
+    sidx = rng.integers(0, len(sc), size=(N, K // 32))
+    scales = pv_inputs.bf16_round_f32(sc[sidx].astype(np.float32))
+    x = rng.integers(-5, 6, size=(3, K)).astype(np.float64)
+    want = np.zeros((3, N))
+    for j in range(3):
+        for n in range(N):
+            for g in range(K // 32):
+                want[j, n] += sc[sidx[n, g]] * sum((int(c[n, k]) - 8) * int(x[j, k]) for k in range(32 * g, 32 * g + 32))
+    got = ref.linear(x, ref.dequant_q4(codes, scales))     # float32 weights (exact), fp64 arithmetic
+    assert np.array_equal(got, want)
