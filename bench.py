@@ -38,7 +38,7 @@ MEASURED_TRAFFIC = {
 
 DEFAULTS = {  # workload -> (prefix, gamma, alpha)
     "tiny": (64, 4, 0.7), "7b": (512, 8, 0.8), "8b": (2048, 8, 0.7), "70b": (1024, 8, 0.6),
-    "1b": (1024, 1, 0.7), "70b_v128k": (1024, 8, 0.6),
+    "1b": (1024, 1, 0.7), "70b_v128k": (1024, 8, 0.6), "70b_q4": (1024, 8, 0.6), "8b_q4": (2048, 8, 0.7),
 }
 
 
@@ -58,8 +58,12 @@ def load_model(pv, pv_inputs, shape, max_gamma, kernel_path=0):
     last = t0
     for kind, layer in pv_inputs.iter_tensors(shape):
         cols = pv_inputs.tensor_shape(shape, kind)[-1]
+        q4 = shape.weight_bits == 4 and kind in pv_inputs.Q4_KINDS
         for r0, rows in pv_inputs.iter_row_chunks(shape, kind, layer, m.chunk_rows(cols), scratch=scratch):
-            m.load_weights(kind, layer, r0, rows)
+            if q4:
+                m.load_weights_q4(kind, layer, r0, *pv_inputs.quantize_q4(rows))
+            else:
+                m.load_weights(kind, layer, r0, rows)
             done += rows.size
         if time.time() - last > 20:
             last = time.time()

@@ -78,7 +78,14 @@ typedef struct {
     int32_t page_tokens;  /* tokens per KV page, power of two, >= 16 on the matrix path    */
     int32_t max_gamma;    /* largest block (rows) one verify / prefill chunk may carry, <= 64 */
     int32_t kernel_path;  /* pv_kernel_path                                                */
+    int32_t weight_bits;  /* 0 or 16: matrices stored in `dtype`.  4: the projection matrices and
+                           * the LM head are 4-bit codes with one bf16 scale per 32 input
+                           * features, weight = (code - 8) * scale (the 4-bit target model of the
+                           * paper's Sec. 4.1; format chosen by this library); needs PV_BF16, the
+                           * matrix path, input widths that are multiples of 128, max_gamma <= 16 */
 } pv_model_config;
+
+#define PV_Q4_GROUP 32      /* input features per scale of a 4-bit matrix */
 
 typedef struct pv_model pv_model;   /* immutable once all weights are loaded */
 typedef struct pv_cache pv_cache;   /* one sequence of one stage             */
@@ -112,6 +119,13 @@ void pv_model_destroy(pv_model *m);
  */
 int pv_load_weights(pv_model *m, int32_t kind, int32_t layer, int64_t row_begin, int64_t row_count,
                     const void *host_rows, void *hip_stream);
+
+/* Rows of one matrix of a 4-bit model (kinds WQ, WK, WV, WO, WG, WU, WD, LM_HEAD; every other
+ * tensor of such a model goes through pv_load_weights).  host_codes: [row_count][cols / 2] bytes,
+ * two codes per byte, the even input feature in the low nibble; host_scales: [row_count][cols /
+ * 32] bf16 bit patterns.  Same row, chunk and synchronisation rules as pv_load_weights. */
+int pv_load_weights_q4(pv_model *m, int32_t kind, int32_t layer, int64_t row_begin, int64_t row_count,
+                       const void *host_codes, const void *host_scales, void *hip_stream);
 
 /* d_page_pool / d_workspace: device, 256-byte aligned.  The new cache is empty (length 0,
  * pending unknown) with the identity page table. */

@@ -26,7 +26,7 @@ class pv_model_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "ffn_dim", "vocab")] + \
                [("rms_eps", ctypes.c_double), ("rope_base", ctypes.c_double)] + \
-               [(n, ctypes.c_int32) for n in ("dtype", "page_tokens", "max_gamma", "kernel_path")]
+               [(n, ctypes.c_int32) for n in ("dtype", "page_tokens", "max_gamma", "kernel_path", "weight_bits")]
 
 
 EXPORTS = [
@@ -34,7 +34,7 @@ EXPORTS = [
     "pv_cache_create", "pv_cache_destroy", "pv_cache_set_page_table", "pv_prefill", "pv_verify",
     "pv_verify_async", "pv_verify_wait", "pv_rollback", "pv_cache_len", "pv_cache_set_pending",
     "pv_debug_logits", "pv_debug_pred", "pv_cache_export", "pv_step_bytes", "pv_strerror", "pv_last_error",
-    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_cache_use_graphs",
+    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_cache_use_graphs", "pv_load_weights_q4",
 ]
 
 _lib = None
@@ -55,6 +55,7 @@ def lib():
         L.pv_model_create.argtypes = [cfgp, vp, sz, vp, sz, P(vp)]
         L.pv_model_destroy.argtypes = [vp]; L.pv_model_destroy.restype = None
         L.pv_load_weights.argtypes = [vp, i32, i32, i64, i64, vp, vp]
+        L.pv_load_weights_q4.argtypes = [vp, i32, i32, i64, i64, vp, vp, vp]
         L.pv_cache_create.argtypes = [vp, vp, sz, vp, sz, i32, P(vp)]
         L.pv_cache_destroy.argtypes = [vp]; L.pv_cache_destroy.restype = None
         L.pv_cache_set_page_table.argtypes = [vp, vp, i32, vp]
@@ -109,12 +110,13 @@ class Model:
 
     def __init__(self, shape, max_gamma=16, kernel_path=PATH_AUTO, device="cuda:0"):
         """shape: object with n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab,
-        rms_eps, rope_base, dtype ("f32"|"bf16"), page_tokens."""
+        rms_eps, rope_base, dtype ("f32"|"bf16"), page_tokens and optionally weight_bits (16 | 4)."""
         self.L, self.shape, self.device = lib(), shape, torch.device(device)
         self.cfg = pv_model_config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads,
                                    shape.head_dim, shape.ffn_dim, shape.vocab, shape.rms_eps, shape.rope_base,
                                    PV_BF16 if shape.dtype == "bf16" else PV_F32, shape.page_tokens,
-                                   max_gamma, kernel_path)
+                                   max_gamma, kernel_path, 4 if getattr(shape, "weight_bits", 16) == 4 else 16)
+        self.weight_bits = self.cfg.weight_bits
         wb, sb = ctypes.c_size_t(), ctypes.c_size_t()
         _check(self.L.pv_model_bytes(ctypes.byref(self.cfg), ctypes.byref(wb), ctypes.byref(sb)), "pv_model_bytes")
         with torch.cuda.device(self.device):
@@ -135,13 +137,23 @@ class Model:
             _check(self.L.pv_load_weights(self.h, KINDS[kind], layer, row_begin, rows.shape[0],
                                           rows.ctypes.data, _stream_ptr(stream)), f"pv_load_weights({kind},{layer})")
 
+    def load_weights_q4(self, kind, layer, row_begin, codes, scales, stream=None):
+        """Rows of a matrix of a 4-bit model: codes uint8 [row_count, in_features / 2] (even feature in
+        the low nibble), scales uint16 = bf16 bits [row_count, in_features / 32]."""
+        codes, scales = np.ascontiguousarray(codes), np.ascontiguousarray(scales)
+        assert codes.dtype == np.uint8 and scales.dtype == np.uint16 and codes.shape[0] == scales.shape[0]
+        assert codes.shape[1] * 2 == scales.shape[1] * 32
+        with torch.cuda.device(self.device):
+            _check(self.L.pv_load_weights_q4(self.h, KINDS[kind], layer, row_begin, codes.shape[0], codes.ctypes.data,
+                                             scales.ctypes.data, _stream_ptr(stream)), f"pv_load_weights_q4({kind},{layer})")
+
     def chunk_rows(self, in_features):
         """Largest row count (multiple of 16) whose chunk fits the staging buffer."""
         per_row = in_features * self.np_dtype().itemsize
         return max(16, (self.staging_bytes // per_row) // 16 * 16)
 
     def close(self):
-        if self.h:
+        if getattr(self, "h", None):
             self.L.pv_model_destroy(self.h); self.h = None
 
     def __del__(self):

@@ -56,6 +56,12 @@ static int check_config(const pv_model_config *c)
     if (path != PV_PATH_VECTOR && path != PV_PATH_MATRIX) { pv_set_error("bad kernel_path"); return PV_EINVAL; }
     const int qd = c->n_q_heads * c->head_dim;
     if (c->d_model % 4 || c->ffn_dim % 4 || qd % 4) { pv_set_error("d_model, ffn_dim, q_dim must be multiples of 4"); return PV_EINVAL; }
+    if (c->weight_bits != 0 && c->weight_bits != 16 && c->weight_bits != 4) { pv_set_error("weight_bits must be 0, 16 or 4"); return PV_EINVAL; }
+    if (c->weight_bits == 4) {
+        if (path < PV_PATH_MATRIX || c->dtype != PV_BF16) { pv_set_error("4-bit weights need bf16 storage and the matrix path"); return PV_EINVAL; }
+        if (c->d_model % 128 || c->ffn_dim % 128 || qd % 128) { pv_set_error("4-bit weights: d_model, ffn_dim, q_dim must be multiples of 128"); return PV_EINVAL; }
+        if (c->max_gamma > 16) { pv_set_error("4-bit weights: max_gamma must be <= 16"); return PV_EINVAL; }
+    }
     if (path >= PV_PATH_MATRIX) {
         if (c->dtype != PV_BF16) { pv_set_error("matrix path needs bf16 storage"); return PV_EINVAL; }
         if (c->d_model % 32 || c->ffn_dim % 32 || qd % 32 || c->vocab % 16 || (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) || c->page_tokens < 16) {
@@ -90,7 +96,8 @@ static size_t layout_arena(const pv_model_config *c, pv_model *m)
     auto place = [&](int kind, int layer) {
         int64_t r, k; tensor_dims(c, kind, &r, &k);
         pv_tensor_ref t; t.off = off; t.rows = r; t.cols = k; t.loaded_rows = 0; t.strip_mul = 1; t.strip_add = 0;
-        off = align_up(off + (size_t)r * k * elt, 256);
+        const size_t bytes = (c->weight_bits == 4 && pv_is_q4_kind(kind)) ? (size_t)(r / 16) * (k / 128) * PV_Q4_BATCH : (size_t)r * k * elt;
+        off = align_up(off + bytes, 256);
         if (m) { if (layer < 0) m->global[kind] = t; else m->layer[(size_t)layer * PV_T_NKINDS + kind] = t; }
     };
     place(PV_T_EMBED, -1);
@@ -137,6 +144,7 @@ extern "C" int pv_model_create(const pv_model_config *cfg, void *d_weights, size
     pv_model *m = new (std::nothrow) pv_model();
     if (!m) return PV_ENOMEM;
     m->cfg = *cfg; m->path = resolve_path(cfg); m->elt = cfg->dtype == PV_BF16 ? 2 : 4;
+    m->wbits = cfg->weight_bits == 4 ? 4 : 16;
     m->d_weights = (char *)d_weights; m->weight_bytes = weight_bytes;
     m->d_staging = (char *)d_staging; m->staging_bytes = staging_bytes;
     m->layer = (pv_tensor_ref *)calloc((size_t)cfg->n_layers * PV_T_NKINDS, sizeof(pv_tensor_ref));
@@ -175,6 +183,7 @@ extern "C" int pv_load_weights(pv_model *m, int32_t kind, int32_t layer, int64_t
     if (!global && (layer < 0 || layer >= m->cfg.n_layers)) { pv_set_error("bad layer %d", layer); return PV_EINVAL; }
     pv_tensor_ref &t = global ? m->global[kind] : m->layer[(size_t)layer * PV_T_NKINDS + kind];
     if (row_begin < 0 || row_count <= 0 || row_begin + row_count > t.rows) { pv_set_error("rows [%lld, +%lld) outside tensor of %lld rows", (long long)row_begin, (long long)row_count, (long long)t.rows); return PV_ERANGE; }
+    if (m->wbits == 4 && pv_is_q4_kind(kind)) { pv_set_error("tensor kind %d of a 4-bit model is loaded with pv_load_weights_q4", kind); return PV_EINVAL; }
     hipStream_t s = (hipStream_t)hip_stream;
     const size_t nbytes = (size_t)row_count * t.cols * m->elt;
     const bool tiled = m->path >= PV_PATH_MATRIX && t.rows > 1 && kind != PV_T_EMBED;
@@ -189,6 +198,30 @@ extern "C" int pv_load_weights(pv_model *m, int32_t kind, int32_t layer, int64_t
         if (rc != PV_OK) return rc;
         PV_HIP(hipStreamSynchronize(s));
     }
+    t.loaded_rows += row_count;
+    return PV_OK;
+}
+
+extern "C" int pv_load_weights_q4(pv_model *m, int32_t kind, int32_t layer, int64_t row_begin, int64_t row_count,
+                                  const void *host_codes, const void *host_scales, void *hip_stream)
+{
+    if (!m || !host_codes || !host_scales) { pv_set_error("null pointer"); return PV_EINVAL; }
+    if (m->wbits != 4) { pv_set_error("not a 4-bit model"); return PV_ESTATE; }
+    if (kind < 0 || kind >= PV_T_NKINDS || !pv_is_q4_kind(kind)) { pv_set_error("tensor kind %d is not stored in 4 bit", kind); return PV_EINVAL; }
+    const bool global = kind == PV_T_LM_HEAD;
+    if (!global && (layer < 0 || layer >= m->cfg.n_layers)) { pv_set_error("bad layer %d", layer); return PV_EINVAL; }
+    pv_tensor_ref &t = global ? m->global[kind] : m->layer[(size_t)layer * PV_T_NKINDS + kind];
+    if (row_begin < 0 || row_count <= 0 || row_begin + row_count > t.rows) { pv_set_error("rows [%lld, +%lld) outside tensor of %lld rows", (long long)row_begin, (long long)row_count, (long long)t.rows); return PV_ERANGE; }
+    if ((row_begin | row_count) & 15) { pv_set_error("matrix path: row_begin and row_count must be multiples of 16"); return PV_EINVAL; }
+    const size_t cbytes = (size_t)row_count * (t.cols / 2), sbytes = (size_t)row_count * (t.cols / PV_Q4_GROUP) * 2;
+    const size_t soff = align_up(cbytes, 256);
+    if (soff + sbytes > m->staging_bytes) { pv_set_error("chunk of %zu bytes exceeds staging buffer of %zu", soff + sbytes, m->staging_bytes); return PV_ENOMEM; }
+    hipStream_t s = (hipStream_t)hip_stream;
+    PV_HIP(hipMemcpyAsync(m->d_staging, host_codes, cbytes, hipMemcpyHostToDevice, s));
+    PV_HIP(hipMemcpyAsync(m->d_staging + soff, host_scales, sbytes, hipMemcpyHostToDevice, s));
+    int rc = pv_mat_repack_q4(m, t, kind, row_begin, row_count, soff, s);
+    if (rc != PV_OK) return rc;
+    PV_HIP(hipStreamSynchronize(s));
     t.loaded_rows += row_count;
     return PV_OK;
 }
@@ -419,6 +452,7 @@ extern "C" int pv_profile_read(pv_cache *c, double *total_ms, int64_t *launches,
     case PV_PROF_LMHEAD: b = (uint64_t)f.vocab * d * e; break;
     default: break;
     }
+    if (c->m->wbits == 4 && c->prof_kind != PV_PROF_ATTENTION) b = b / (16 * 128 * e) * PV_Q4_BATCH;   // 16 x 128 weights per batch
     if (total_ms) *total_ms = c->prof_ms;
     if (launches) *launches = c->prof_launches;
     if (bytes_per_launch) *bytes_per_launch = b;
@@ -627,7 +661,8 @@ extern "C" int pv_step_bytes(const pv_cache *c, int32_t gamma, uint64_t *bytes)
         if (k == PV_T_EMBED) continue;
         int64_t r, cc; tensor_dims(&f, k, &r, &cc);
         const bool global = k == PV_T_FINAL_NORM || k == PV_T_LM_HEAD;
-        w += (uint64_t)r * cc * m->elt * (global ? 1 : f.n_layers);
+        const uint64_t tb = (m->wbits == 4 && pv_is_q4_kind(k)) ? (uint64_t)(r / 16) * (cc / 128) * PV_Q4_BATCH : (uint64_t)r * cc * m->elt;
+        w += tb * (global ? 1 : f.n_layers);
     }
     const uint64_t kv_tok = (uint64_t)f.n_layers * 2 * f.n_kv_heads * f.head_dim * m->elt;
     *bytes = w + kv_tok * (uint64_t)(c->len + gamma) + kv_tok * (uint64_t)gamma;

@@ -44,6 +44,7 @@ struct pv_tensor_ref {
 struct pv_model {
     pv_model_config cfg;
     int path;                   // PV_PATH_VECTOR or PV_PATH_MATRIX (resolved)
+    int wbits;                  // 16, or 4: projection matrices and LM head as codes + group scales
     int elt;                    // bytes per stored element
     char *d_weights; size_t weight_bytes;
     char *d_staging; size_t staging_bytes;
@@ -125,6 +126,17 @@ __host__ __device__ static inline size_t pv_v_off(const pv_kv_geom &g, int t, in
 int pv_vec_run_block(pv_cache *c, hipStream_t s);        // pv_kernels_vector.hip
 int pv_mat_run_block(pv_cache *c, hipStream_t s);        // pv_kernels_matrix.hip
 int pv_mat_repack(const pv_model *m, const pv_tensor_ref &t, int kind, int64_t row_begin, int64_t row_count, hipStream_t s);
+int pv_mat_repack_q4(const pv_model *m, const pv_tensor_ref &t, int kind, int64_t row_begin, int64_t row_count, size_t scales_off, hipStream_t s);
+
+// 4-bit matrices: a strip (16 output features) is a run of cols/128 batches of PV_Q4_BATCH bytes:
+// 4 K-tiles of codes, [lane 0..63][tile 0..3] dwords (a dword = the lane's 8 consecutive k of its
+// row), then the 64 bf16 scales of the batch as [lane/16 = feature group][tile][feature % 4].
+#define PV_Q4_BATCH 1152
+static inline bool pv_is_q4_kind(int kind)
+{
+    return kind == PV_T_WQ || kind == PV_T_WK || kind == PV_T_WV || kind == PV_T_WO || kind == PV_T_WG || kind == PV_T_WU ||
+           kind == PV_T_WD || kind == PV_T_LM_HEAD;
+}
 size_t pv_mat_part_floats(const pv_model *m, int rows_cap, int max_tokens);
 size_t pv_attn_part_floats(const pv_model *m, int rows_cap, int max_tokens);
 int pv_mat_attention_init(int head_dim);

@@ -98,6 +98,53 @@ int pv_mat_repack(const pv_model *m, const pv_tensor_ref &t, int kind, int64_t r
     return PV_OK;
 }
 
+// Rows of a 4-bit matrix, row-major in staging (codes: K/8 dwords per row, a dword = 8 consecutive
+// k, low nibble first; scales: K/32 bf16 per row), into the batched strip layout (pv_internal.h).
+// One thread moves one dword of codes; the thread of a tile's first dword also moves its scale.
+__global__ void k_repack_q4(const uint32_t *codes, const uint16_t *scales, char *dst, int64_t row_begin, int64_t row_count,
+                            int K, int perm, int head_dim, int strip_mul, int strip_add)
+{
+    const int kd = K / 8, nb4 = K / 128;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= row_count * kd) return;
+    const int64_t nl = idx / kd, n = row_begin + nl;
+    const int w = (int)(idx % kd), kt = w >> 2, q = w & 3;      // tile, feature-of-k group
+    int64_t strip; int i;
+    if (perm == PERM_ROPE) {
+        const int half = head_dim / 2, e = (int)(n % head_dim);
+        const int64_t h = n / head_dim;
+        const int side = e >= half, p = e - side * half;
+        strip = h * (head_dim / 16) + p / 8; i = (p & 7) + 8 * side;
+    } else if (perm == PERM_GATEUP) {
+        strip = n / 8; i = (int)(n & 7) + 8 * strip_add;
+    } else {
+        strip = (n / 16) * strip_mul + strip_add; i = (int)(n & 15);
+    }
+    char *batch = dst + ((size_t)strip * nb4 + (kt >> 2)) * PV_Q4_BATCH;
+    const int u = kt & 3;
+    // the lane's 8 codes c0..c7 (source: c0 in the lowest nibble) are stored as
+    // (c0 | c2 << 4 | c4 << 8 | c6 << 12) | (c1 | c3 << 4 | c5 << 8 | c7 << 12) << 16,
+    // so that one shift and one mask give the bf16 pair (k = 2t, 2t + 1) of operand dword t
+    const uint32_t src = codes[idx];
+    uint32_t even = 0, odd = 0;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) { even |= ((src >> (8 * t)) & 0xFu) << (4 * t); odd |= ((src >> (8 * t + 4)) & 0xFu) << (4 * t); }
+    ((uint32_t *)batch)[(i + 16 * q) * 4 + u] = even | (odd << 16);
+    if (q == 0) ((uint16_t *)(batch + 1024))[((i >> 2) * 4 + u) * 4 + (i & 3)] = scales[nl * (K / 32) + kt];
+}
+
+int pv_mat_repack_q4(const pv_model *m, const pv_tensor_ref &t, int kind, int64_t row_begin, int64_t row_count, size_t scales_off, hipStream_t s)
+{
+    int perm = PERM_NONE, mul = 1, add = 0;
+    if (kind == PV_T_WQ || kind == PV_T_WK) perm = PERM_ROPE;
+    else if (kind == PV_T_WG || kind == PV_T_WU) { perm = PERM_GATEUP; add = t.strip_add; }
+    const int64_t n = row_count * (t.cols / 8);
+    k_repack_q4<<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const uint32_t *)m->d_staging, (const uint16_t *)(m->d_staging + scales_off),
+                                                            m->d_weights + t.off, row_begin, row_count, (int)t.cols, perm, m->cfg.head_dim, mul, add);
+    PV_HIP(hipGetLastError());
+    return PV_OK;
+}
+
 // Block set-up on the matrix path: embedding rows -> x, first operand, first sum of squares;
 // rotary table for positions len .. len+rows-1.
 template <int NB>
@@ -135,13 +182,21 @@ k_mat_begin(const pv_dev_state *st, const uint16_t *embed, const uint16_t *gain,
 // K assignment: contiguous runs of batches per wave, or batch b to wave b % NW (the workgroup
 // then reads its strips as advancing windows).
 // ------------------------------------------------------------------------------------------
-template <int NB, int CT, int S, int EPI, int NW>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NB == 1 ? 8 : 4)))   // NB == 1: <= 64 VGPRs, two 16-wave workgroups per CU
+//
+// WB == 4: the strip is a run of batches of 4-bit codes and bf16 group scales (one scale per
+// output feature and K-tile).  A code c enters the matrix core as the bf16 number 16 + c (the
+// nibble OR-ed into the top mantissa bits of 16.0 = 0x4180: exact).  Per K-tile the accumulator
+// is started by the product of an all -24 operand with the activation tile (= -24 x column
+// sums, shared by the S strips), so that the codes' product on top of it is
+// sum_k (c_k - 8) * x_k; the vector ALU only multiplies that by the tile's scale and adds.
+template <int NB, int CT, int S, int EPI, int NW, int WB = 16>
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((NB == 1 && S == 1 && WB == 16) ? 8 : 4)))   // packed bf16 rows, one strip: <= 64 VGPRs, two 16-wave workgroups per CU
 k_gemm(const gemm_args a)
 {
-    static_assert(NB == 2 || (CT == 1 && S == 1), "packed rows: one tile, one strip");
+    static_assert(NB == 2 || CT == 1, "packed rows come in one tile");
     static_assert(S <= NW, "one epilogue wave per strip");
-    constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : 4;
+    static_assert(WB == 16 || (WB == 4 && CT == 1), "4-bit weights: one column tile");
+    constexpr int U = (WB == 4) ? 8 : (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : 4;   // 4-bit: two batches of 4 tiles per step, for bytes in flight
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
     constexpr bool PARK = (S == 1 && CT == 1);       // epilogue inputs fetched early and parked in LDS
     const int strip0 = blockIdx.x * S, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -175,12 +230,43 @@ k_gemm(const gemm_args a)
     }
 
     uint4 ra[S][U], rb[CT][U], rc[CT][U];
+    uint4 qc[S][2], qs[S][2][2];                     // WB == 4: per strip and batch the lane's codes of 4 tiles and its 4 x 4 scales
+    const size_t qstrip = (size_t)(KT / 4) * PV_Q4_BATCH;
+    const char *Aq = (const char *)a.W + (size_t)strip0 * qstrip;
+    // one K-tile of 4-bit weights of strip si: codes dword cw, scale pairs s01 / s23, activation tile bh (+ bl), T0 = -24 x column sums
+    auto q4_tile = [&](int si, uint32_t cw, uint32_t s01, uint32_t s23, const uint4 &bh, const uint4 &bl, const f32x4 &T0) {
+        // operand dword t = bf16 pair (16 + c_2t, 16 + c_2t+1): nibble t of each half into the top mantissa bits of 16.0
+        const uint4 wa = make_uint4(((cw << 3) & 0x00780078u) | 0x41804180u, ((cw >> 1) & 0x00780078u) | 0x41804180u,
+                                    ((cw >> 5) & 0x00780078u) | 0x41804180u, ((cw >> 9) & 0x00780078u) | 0x41804180u);
+        f32x4 T = mfma16(wa, bh, T0);
+        if (NB == 2) T = mfma16(wa, bl, T);
+        acc[si][0][0] = fmaf(__uint_as_float(s01 << 16), T[0], acc[si][0][0]);
+        acc[si][0][1] = fmaf(__uint_as_float(s01 & 0xFFFF0000u), T[1], acc[si][0][1]);
+        acc[si][0][2] = fmaf(__uint_as_float(s23 << 16), T[2], acc[si][0][2]);
+        acc[si][0][3] = fmaf(__uint_as_float(s23 & 0xFFFF0000u), T[3], acc[si][0][3]);
+    };
+    // -24 in every element: its product with the activation tile starts the accumulator at
+    // -24 x (column sums), on top of which the codes' product lands as sum (c - 8) x
+    const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
     auto load_batch = [&](int t) {
+        if (WB == 4) {
+#pragma unroll
+            for (int si = 0; si < S; ++si)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const char *p = Aq + (strip0 + si < a.nstrips ? (size_t)si * qstrip : 0) + (size_t)((t >> 2) + h) * PV_Q4_BATCH;
+                    qc[si][h] = *(const uint4 *)(p + lane * 16);
+                    qs[si][h][0] = *(const uint4 *)(p + 1024 + (lane >> 4) * 32);
+                    qs[si][h][1] = *(const uint4 *)(p + 1024 + (lane >> 4) * 32 + 16);
+                }
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const size_t o = (size_t)(t + u) * 64;
+            if (WB == 16) {
 #pragma unroll
-            for (int si = 0; si < S; ++si) ra[si][u] = A[so[si] + o];
+                for (int si = 0; si < S; ++si) ra[si][u] = A[so[si] + o];
+            }
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 rb[ct][u] = B[(size_t)(2 * ct) * arr + o];
@@ -189,6 +275,21 @@ k_gemm(const gemm_args a)
         }
     };
     auto use_batch = [&]() {
+        if (WB == 4) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                f32x4 T0 = {0.f, 0.f, 0.f, 0.f};
+                T0 = mfma16(neg24, rb[0][u], T0);
+                if (NB == 2) T0 = mfma16(neg24, rc[0][u], T0);
+#pragma unroll
+                for (int si = 0; si < S; ++si) {
+                    const uint4 c4 = qc[si][u >> 2], sq = qs[si][u >> 2][(u >> 1) & 1];
+                    const uint32_t cw = (u & 3) == 0 ? c4.x : (u & 3) == 1 ? c4.y : (u & 3) == 2 ? c4.z : c4.w;
+                    q4_tile(si, cw, (u & 1) ? sq.z : sq.x, (u & 1) ? sq.w : sq.y, rb[0][u], rc[0][u], T0);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -222,7 +323,27 @@ k_gemm(const gemm_args a)
         load_batch(b * U);
         use_batch();
     }
-    if (wave == NW - 1) {
+    if (WB == 4 && wave == NW - 1 && nbat * U < KT) {    // an odd batch of 4 tiles is left over
+        const int t = nbat * U;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const size_t o = (size_t)(t + u) * 64;
+            const uint4 bh = B[o];
+            uint4 bl = bh;
+            if (NB == 2) bl = B[arr + o];
+            f32x4 T0 = {0.f, 0.f, 0.f, 0.f};
+            T0 = mfma16(neg24, bh, T0);
+            if (NB == 2) T0 = mfma16(neg24, bl, T0);
+#pragma unroll
+            for (int si = 0; si < S; ++si) {
+                const char *p = Aq + (strip0 + si < a.nstrips ? (size_t)si * qstrip : 0) + (size_t)(t >> 2) * PV_Q4_BATCH;
+                const uint32_t cw = ((const uint32_t *)p)[lane * 4 + u];
+                const uint2 sq = *(const uint2 *)(p + 1024 + (lane >> 4) * 32 + u * 8);
+                q4_tile(si, cw, sq.x, sq.y, bh, bl, T0);
+            }
+        }
+    }
+    if (WB == 16 && wave == NW - 1) {
         for (int t = nbat * U; t < KT; ++t) {
             const size_t o = (size_t)t * 64;
 #pragma unroll
@@ -306,7 +427,16 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
     gemm_args ga = g;
     ga.nstrips = strips;
     ga.interleave = g.ktiles > 128;                          // long strips: measured 0.3 % faster per step, short ones 0.3 % slower
-    if constexpr (NB == 2) {
+    if (m->wbits == 4) {
+        if constexpr (CT == 1) {
+            // two strips per workgroup share every activation tile (4 KiB per 2.25 KiB of weights otherwise)
+            if (NB == 1 && strips >= 512 && g.ktiles >= 64) k_gemm<1, 1, 2, EPI, 8, 4><<<(strips + 1) / 2, 512, 0, s>>>(ga);
+            else if (g.ktiles >= 64) k_gemm<NB, 1, 1, EPI, 16, 4><<<strips, 1024, 0, s>>>(ga);
+            else k_gemm<NB, 1, 1, EPI, 8, 4><<<strips, 512, 0, s>>>(ga);
+        } else {
+            pv_set_error("4-bit weights: at most 16 rows per block"); return PV_ERANGE;
+        }
+    } else if constexpr (NB == 2) {
         // Strips per workgroup: with enough strips to fill the machine anyway, the 2 CT operand
         // tiles per batch tile are matched by as many weight tiles (S = 2 or 4); a GEMM with few
         // strips keeps one strip per workgroup and more waves instead.

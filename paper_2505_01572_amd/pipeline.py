@@ -218,8 +218,12 @@ def load_stage_model(pv, pv_inputs, shp, max_gamma=16):
     scratch = pinned.numpy().view(m.np_dtype)
     for kind, layer in pv_inputs.iter_tensors(shp):
         cols = pv_inputs.tensor_shape(shp, kind)[-1]
+        q4 = getattr(shp, "weight_bits", 16) == 4 and kind in pv_inputs.Q4_KINDS
         for r0, rows in pv_inputs.iter_row_chunks(shp, kind, layer, m.chunk_rows(cols), scratch=scratch):
-            m.load_weights(kind, layer, r0, rows)
+            if q4:
+                m.load_weights_q4(kind, layer, r0, *pv_inputs.quantize_q4(rows))
+            else:
+                m.load_weights(kind, layer, r0, rows)
     return m
 
 

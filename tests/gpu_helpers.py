@@ -16,8 +16,12 @@ def gpu_model(shape, gains="ones", max_gamma=16, kernel_path=pv.PATH_AUTO, overr
             for r0 in range(0, arr.shape[0], step):
                 m.load_weights(kind, layer, r0, arr[r0:r0 + step])
             continue
+        q4 = getattr(shape, "weight_bits", 16) == 4 and kind in pv_inputs.Q4_KINDS
         for r0, rows in pv_inputs.iter_row_chunks(shape, kind, layer, m.chunk_rows(cols), gains=gains):
-            m.load_weights(kind, layer, r0, rows)
+            if q4:
+                m.load_weights_q4(kind, layer, r0, *pv_inputs.quantize_q4(rows))
+            else:
+                m.load_weights(kind, layer, r0, rows)
     return m
 
 
@@ -40,9 +44,15 @@ def paired_models(shape, max_gamma=16, real="f64"):
     for kind, layer in pv_inputs.iter_tensors(shape):
         tshape = pv_inputs.tensor_shape(shape, kind)
         arr = pv_inputs.fill_tensor(shape, kind, layer).reshape(tshape)
-        rm.set_tensor(kind, layer, arr)
         a2 = arr.reshape(-1, tshape[-1])
         step = gm.chunk_rows(tshape[-1])
+        if getattr(shape, "weight_bits", 16) == 4 and kind in pv_inputs.Q4_KINDS:
+            codes, scales = pv_inputs.quantize_q4(a2)           # both sides get the same codes and scales
+            rm.set_tensor(kind, layer, ref.dequant_q4(codes, scales))
+            for r0 in range(0, a2.shape[0], step):
+                gm.load_weights_q4(kind, layer, r0, codes[r0:r0 + step], scales[r0:r0 + step])
+            continue
+        rm.set_tensor(kind, layer, arr)
         for r0 in range(0, a2.shape[0], step):
             gm.load_weights(kind, layer, r0, a2[r0:r0 + step])
     return gm, rm
