@@ -98,4 +98,5 @@ CONFIGS = {
     # 4-bit variants of the verifier shapes (the paper runs its 70B model in 4 bit, Sec. 4.1)
     "70b_q4": ModelShape("70b_q4", 80, 8192, 64, 8, 128, 28672, 32000, seed=1003, weight_bits=4),
     "8b_q4": ModelShape("8b_q4", 32, 4096, 32, 8, 128, 14336, 128256, rope_base=500000.0, seed=1002, weight_bits=4),
+    "70b_v128k_q4": ModelShape("70b_v128k_q4", 80, 8192, 64, 8, 128, 28672, 128256, rope_base=500000.0, seed=1005, weight_bits=4),
 }
