@@ -202,12 +202,38 @@ __device__ inline void attn_merge_unit(const attn_args &a, int j, int aq, int mp
     const size_t unit0 = ((size_t)kvh * mp_count + mp) * a.max_chunks;
     float *sh_m = smem;                                              // [NT]
     float (*sh_acc)[TPC][5] = (float (*)[TPC][5])(smem + NT);        // [NG][TPC][5]
-    // global max over chunks: with few chunks every thread reads them all (broadcast loads, no
-    // barrier); with many, each thread looks at chunks t, t+NT, ... and a tree in LDS finishes
-    float M = -INFINITY;
-    if (nchunks <= 32) {
-        for (int c = 0; c < nchunks; ++c) M = fmaxf(M, a.part_ml[((unit0 + c) * 32 + row) * 2]);
+    const int t = tid % TPC, cg = tid / TPC;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f}, L = 0.f;
+    if (nchunks <= 64) {
+        // Up to 64 chunks: lane c of every wave holds chunk c's (max, sum); the global max, the
+        // weights and the total come from wave shuffles (every wave redundantly, no barrier), and
+        // the partial outputs are then fetched four chunks at a time with nothing depending on them.
+        const int lane = tid & 63;
+        float2 ml = make_float2(-INFINITY, 0.f);
+        if (lane < nchunks) ml = *(const float2 *)(a.part_ml + ((unit0 + lane) * 32 + row) * 2);
+        float M = ml.x;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
+        const float wl = (ml.x == -INFINITY) ? 0.f : expf(ml.x - M);
+        L = ml.y * wl;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) L += __shfl_xor(L, o, 64);
+        for (int base = 0; base < nchunks; base += 4 * NG) {      // same trip count in every lane: the shuffles below need all lanes
+            float4 o[4]; float w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = base + cg + u * NG, cc = c < nchunks ? c : 0;
+                o[u] = *(const float4 *)(a.part_o + ((unit0 + cc) * 32 + row) * HD + 4 * t);
+                w[u] = __shfl(wl, cc, 64);
+                if (c >= nchunks) w[u] = 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { acc[0] += w[u] * o[u].x; acc[1] += w[u] * o[u].y; acc[2] += w[u] * o[u].z; acc[3] += w[u] * o[u].w; }
+        }
+        if (cg != 0) L = 0.f;                     // the total is added up over the chunk groups below: count it once
     } else {
+        // many chunks: each thread looks at chunks tid, tid+NT, ... and a tree in LDS finishes the max
+        float M = -INFINITY;
         for (int c = tid; c < nchunks; c += NT) M = fmaxf(M, a.part_ml[((unit0 + c) * 32 + row) * 2]);
         sh_m[tid] = M;
         __syncthreads();
@@ -216,15 +242,13 @@ __device__ inline void attn_merge_unit(const attn_args &a, int j, int aq, int mp
             __syncthreads();
         }
         M = sh_m[0];
-    }
-    const int t = tid % TPC, cg = tid / TPC;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f}, L = 0.f;
-    for (int c = cg; c < nchunks; c += NG) {
-        const float *pm = a.part_ml + ((unit0 + c) * 32 + row) * 2;
-        const float w = (pm[0] == -INFINITY) ? 0.f : expf(pm[0] - M);
-        L += pm[1] * w;
-        const float4 o = *(const float4 *)(a.part_o + ((unit0 + c) * 32 + row) * HD + 4 * t);
-        acc[0] += w * o.x; acc[1] += w * o.y; acc[2] += w * o.z; acc[3] += w * o.w;
+        for (int c = cg; c < nchunks; c += NG) {
+            const float *pm = a.part_ml + ((unit0 + c) * 32 + row) * 2;
+            const float w = (pm[0] == -INFINITY) ? 0.f : expf(pm[0] - M);
+            L += pm[1] * w;
+            const float4 o = *(const float4 *)(a.part_o + ((unit0 + c) * 32 + row) * HD + 4 * t);
+            acc[0] += w * o.x; acc[1] += w * o.y; acc[2] += w * o.z; acc[3] += w * o.w;
+        }
     }
     sh_acc[cg][t][0] = acc[0]; sh_acc[cg][t][1] = acc[1]; sh_acc[cg][t][2] = acc[2]; sh_acc[cg][t][3] = acc[3]; sh_acc[cg][t][4] = L;
     __syncthreads();
