@@ -52,29 +52,31 @@ __device__ inline void emit_x(int lane, int rows, int strip, int d, const float 
 // in two halves so that the caller can put its main loop between issue and use.  Thread `tid`
 // of `nthreads` takes the float4 groups tid, tid+nthreads, ... (all loads independent: a serial
 // chain of L2 round trips would cost more than the weight stream it sits beside).
-struct ssq_loads { float4 v[2]; };
+template <int N = 2> struct ssq_loads { float4 v[N]; };   // N float4 groups per thread go out at once
 
-__device__ inline void ssq_issue(const float *ssq, int parts, int tid, int nthreads, ssq_loads &L)
+template <int N>
+__device__ inline void ssq_issue(const float *ssq, int parts, int tid, int nthreads, ssq_loads<N> &L)
 {
     const float4 *q = (const float4 *)ssq;
     const int n4 = parts * 4;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) { const int i = tid + u * nthreads; L.v[u] = q[i < n4 ? i : 0]; }   // no branch: masked in ssq_finish
+    for (int u = 0; u < N; ++u) { const int i = tid + u * nthreads; L.v[u] = q[i < n4 ? i : 0]; }   // no branch: masked in ssq_finish
 }
 
-// Second half: add up (plus any groups beyond the first two per thread), then combine the lanes
+// Second half: add up (plus any groups beyond the first N per thread), then combine the lanes
 // of the wave that hold the same rows (equal lane % 4).  On return lanes 0..3 hold the wave's
 // sums for rows 4*lane .. 4*lane+3.
-__device__ inline float4 ssq_finish(const float *ssq, int parts, int tid, int nthreads, const ssq_loads &L)
+template <int N>
+__device__ inline float4 ssq_finish(const float *ssq, int parts, int tid, int nthreads, const ssq_loads<N> &L)
 {
     const float4 *q = (const float4 *)ssq;
     const int n4 = parts * 4;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < N; ++u) {
         if (tid + u * nthreads < n4) { s.x += L.v[u].x; s.y += L.v[u].y; s.z += L.v[u].z; s.w += L.v[u].w; }
     }
-    for (int i = tid + 2 * nthreads; i < n4; i += nthreads) { const float4 v = q[i]; s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w; }
+    for (int i = tid + N * nthreads; i < n4; i += nthreads) { const float4 v = q[i]; s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w; }
 #pragma unroll
     for (int o = 4; o <= 32; o <<= 1) {
         s.x += __shfl_xor(s.x, o, 64); s.y += __shfl_xor(s.y, o, 64); s.z += __shfl_xor(s.z, o, 64); s.w += __shfl_xor(s.w, o, 64);

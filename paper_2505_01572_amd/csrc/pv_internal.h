@@ -130,7 +130,7 @@ int pv_mat_repack_q4(const pv_model *m, const pv_tensor_ref &t, int kind, int64_
 
 // 4-bit matrices: a strip (16 output features) is a run of cols/128 batches of PV_Q4_BATCH bytes:
 // 4 K-tiles of codes, [lane 0..63][tile 0..3] dwords (a dword = the lane's 8 consecutive k of its
-// row), then the 64 bf16 scales of the batch as [lane/16 = feature group][tile][feature % 4].
+// row), then the 64 bf16 scales of the batch as [feature 0..15][tile 0..3].
 #define PV_Q4_BATCH 1152
 static inline bool pv_is_q4_kind(int kind)
 {

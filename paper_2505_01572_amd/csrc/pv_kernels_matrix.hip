@@ -130,7 +130,7 @@ __global__ void k_repack_q4(const uint32_t *codes, const uint16_t *scales, char 
 #pragma unroll
     for (int t = 0; t < 4; ++t) { even |= ((src >> (8 * t)) & 0xFu) << (4 * t); odd |= ((src >> (8 * t + 4)) & 0xFu) << (4 * t); }
     ((uint32_t *)batch)[(i + 16 * q) * 4 + u] = even | (odd << 16);
-    if (q == 0) ((uint16_t *)(batch + 1024))[((i >> 2) * 4 + u) * 4 + (i & 3)] = scales[nl * (K / 32) + kt];
+    if (q == 0) ((uint16_t *)(batch + 1024))[i * 4 + u] = scales[nl * (K / 32) + kt];
 }
 
 int pv_mat_repack_q4(const pv_model *m, const pv_tensor_ref &t, int kind, int64_t row_begin, int64_t row_count, size_t scales_off, hipStream_t s)
@@ -169,6 +169,41 @@ k_mat_begin(const pv_dev_state *st, const uint16_t *embed, const uint16_t *gain,
     }
 }
 
+// A wave's K walk with DEPTH register buffers: while one batch is used, the loads of the next
+// DEPTH - 1 are in flight.  issue(q, k) starts the loads of the wave's k-th batch into q,
+// consume(q) uses it; between() runs once behind the first loads (work that may wait on older,
+// shorter loads).  Buffers rotate by name, so the steady state is unrolled DEPTH times and every
+// issue in it is unconditional: the wait before a consume then only covers that batch's loads.
+template <int DEPTH, typename Q, typename FI, typename FC, typename FB>
+__device__ inline void k_walk(int cnt, Q &q0, Q &q1, Q &q2, FI issue, FC consume, FB between)
+{
+    if (cnt > 0) issue(q0, 0);
+    if (DEPTH == 3 && cnt > 1) issue(q1, 1);
+    between();
+    int i = 0;
+    if constexpr (DEPTH == 3) {
+        for (; i + 4 < cnt; i += 3) {                // q0 and q1 hold batches i and i + 1, in flight or landed
+            issue(q2, i + 2); consume(q0);
+            issue(q0, i + 3); consume(q1);
+            issue(q1, i + 4); consume(q2);
+        }
+        if (i + 2 < cnt) issue(q2, i + 2);            // at most four batches are left
+        if (i < cnt) consume(q0);
+        if (i + 3 < cnt) issue(q0, i + 3);
+        if (i + 1 < cnt) consume(q1);
+        if (i + 2 < cnt) consume(q2);
+        if (i + 3 < cnt) consume(q0);
+    } else {
+        for (; i + 2 < cnt; i += 2) {                // q0 holds batch i
+            issue(q1, i + 1); consume(q0);
+            issue(q0, i + 2); consume(q1);
+        }
+        if (i + 1 < cnt) issue(q1, i + 1);            // at most two batches are left
+        if (i < cnt) consume(q0);
+        if (i + 1 < cnt) consume(q1);
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // The streaming GEMM: a workgroup owns S adjacent strips, its NW waves split K in batches of U
 // tiles.
@@ -183,20 +218,27 @@ k_mat_begin(const pv_dev_state *st, const uint16_t *embed, const uint16_t *gain,
 // then reads its strips as advancing windows).
 // ------------------------------------------------------------------------------------------
 //
+// DP > 1 (16-bit weights, packed rows, one strip): the wave keeps DP batches in registers and
+// loads ahead (k_walk), for GEMMs with so few strips that resident waves alone leave too few
+// bytes in flight.
+//
 // WB == 4: the strip is a run of batches of 4-bit codes and bf16 group scales (one scale per
-// output feature and K-tile).  A code c enters the matrix core as the bf16 number 16 + c (the
-// nibble OR-ed into the top mantissa bits of 16.0 = 0x4180: exact).  Per K-tile the accumulator
-// is started by the product of an all -24 operand with the activation tile (= -24 x column
-// sums, shared by the S strips), so that the codes' product on top of it is
-// sum_k (c_k - 8) * x_k; the vector ALU only multiplies that by the tile's scale and adds.
-template <int NB, int CT, int S, int EPI, int NW, int WB = 16>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((NB == 1 && S == 1 && WB == 16) ? 8 : 4)))   // packed bf16 rows, one strip: <= 64 VGPRs, two 16-wave workgroups per CU
+// output feature and K-tile); the wave walks them with k_walk, two or three batches deep.  A
+// code c enters the matrix core as the bf16 number 16 + c (the nibble OR-ed into the top
+// mantissa bits of 16.0 = 0x4180: exact).  Per K-tile the accumulator is started by the product
+// of the activation tile with an all -24 operand (= -24 x row sums, shared by the S strips), so
+// that the codes' product on top of it is sum_k (c_k - 8) * x_k; the vector ALU only multiplies
+// that by the tile's scale and adds.  The product is taken transposed (activation rows x
+// features) so that a lane's four results share one feature, hence one scale; the accumulators
+// are turned back on their way through the LDS reduction.
+template <int NB, int CT, int S, int EPI, int NW, int WB = 16, int DP = 1>
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((NB == 1 && S == 1 && WB == 16 && DP == 1) ? 8 : 4)))   // packed bf16 rows, one strip: <= 64 VGPRs, two 16-wave workgroups per CU
 k_gemm(const gemm_args a)
 {
     static_assert(NB == 2 || CT == 1, "packed rows come in one tile");
     static_assert(S <= NW, "one epilogue wave per strip");
     static_assert(WB == 16 || (WB == 4 && CT == 1), "4-bit weights: one column tile");
-    constexpr int U = (WB == 4) ? 8 : (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : 4;   // 4-bit: two batches of 4 tiles per step, for bytes in flight
+    constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : 4;   // tiles per batch (16-bit weights)
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
     constexpr bool PARK = (S == 1 && CT == 1);       // epilogue inputs fetched early and parked in LDS
     const int strip0 = blockIdx.x * S, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -223,50 +265,133 @@ k_gemm(const gemm_args a)
 
     // RMSNorm of the input rows: every wave takes its share of the per-strip sums of squares; the
     // loads go out ahead of the weight stream and are folded in behind its first batch
-    ssq_loads sl[CT];
+    ssq_loads<(WB == 4 && NW <= 8) ? 16 / NW * 2 : 2> sl[CT];   // d up to 8192 without a serial tail of loads
     if (NORM) {
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
     }
 
-    uint4 ra[S][U], rb[CT][U], rc[CT][U];
-    uint4 qc[S][2], qs[S][2][2];                     // WB == 4: per strip and batch the lane's codes of 4 tiles and its 4 x 4 scales
     const size_t qstrip = (size_t)(KT / 4) * PV_Q4_BATCH;
     const char *Aq = (const char *)a.W + (size_t)strip0 * qstrip;
-    // one K-tile of 4-bit weights of strip si: codes dword cw, scale pairs s01 / s23, activation tile bh (+ bl), T0 = -24 x column sums
-    auto q4_tile = [&](int si, uint32_t cw, uint32_t s01, uint32_t s23, const uint4 &bh, const uint4 &bl, const f32x4 &T0) {
-        // operand dword t = bf16 pair (16 + c_2t, 16 + c_2t+1): nibble t of each half into the top mantissa bits of 16.0
-        const uint4 wa = make_uint4(((cw << 3) & 0x00780078u) | 0x41804180u, ((cw >> 1) & 0x00780078u) | 0x41804180u,
-                                    ((cw >> 5) & 0x00780078u) | 0x41804180u, ((cw >> 9) & 0x00780078u) | 0x41804180u);
-        f32x4 T = mfma16(wa, bh, T0);
-        if (NB == 2) T = mfma16(wa, bl, T);
-        acc[si][0][0] = fmaf(__uint_as_float(s01 << 16), T[0], acc[si][0][0]);
-        acc[si][0][1] = fmaf(__uint_as_float(s01 & 0xFFFF0000u), T[1], acc[si][0][1]);
-        acc[si][0][2] = fmaf(__uint_as_float(s23 << 16), T[2], acc[si][0][2]);
-        acc[si][0][3] = fmaf(__uint_as_float(s23 & 0xFFFF0000u), T[3], acc[si][0][3]);
-    };
-    // -24 in every element: its product with the activation tile starts the accumulator at
-    // -24 x (column sums), on top of which the codes' product lands as sum (c - 8) x
-    const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
-    auto load_batch = [&](int t) {
-        if (WB == 4) {
+    if constexpr (WB == 4) {
+        // One batch = 4 K-tiles.  A wave keeps three batches in registers: while one is used the
+        // loads of the next two are in flight, so that the wave always has bytes on the way.
+        // The product is taken transposed here (activation rows x features): all four results
+        // of a lane then belong to one feature, and the lane needs one scale per tile.
+        struct qbatch { uint4 c[S]; uint2 s[S]; uint4 bh[4], bl[NB == 2 ? 4 : 1]; };
+        const int nb4 = KT >> 2, wv = __builtin_amdgcn_readfirstlane(wave);    // batch addresses in scalar registers
+        int first, cnt, bstride;
+        if (a.interleave) { first = wv; bstride = NW; cnt = wv < nb4 ? (nb4 - wv + NW - 1) / NW : 0; }
+        else { const int per = (nb4 + NW - 1) / NW; first = min(nb4, wv * per); cnt = min(nb4, first + per) - first; bstride = 1; }
+        size_t qo[S];
+#pragma unroll
+        for (int si = 0; si < S; ++si) qo[si] = (strip0 + si < a.nstrips) ? (size_t)si * qstrip : 0;
+        auto issue = [&](qbatch &q, int k) {          // k-th batch of this wave
+            const int bt = first + k * bstride;
+#pragma unroll
+            for (int si = 0; si < S; ++si) {
+                const char *p = Aq + qo[si] + (size_t)bt * PV_Q4_BATCH;
+                q.c[si] = *(const uint4 *)(p + lane * 16);
+                q.s[si] = *(const uint2 *)(p + 1024 + (lane & 15) * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const size_t o = (size_t)(bt * 4 + u) * 64;
+                q.bh[u] = B[o];
+                if (NB == 2) q.bl[NB == 2 ? u : 0] = B[arr + o];
+            }
+            asm volatile("" ::: "memory");           // the loads go out here, ahead of the arithmetic that follows
+        };
+        // -24 in every element: its product with the activation tile starts the accumulator at
+        // -24 x (row sums), on top of which the codes' product lands as sum (c - 8) x
+        const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
+        auto consume = [&](const qbatch &q) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                f32x4 T0 = {0.f, 0.f, 0.f, 0.f};
+                T0 = mfma16(q.bh[u], neg24, T0);
+                if (NB == 2) T0 = mfma16(q.bl[NB == 2 ? u : 0], neg24, T0);
+#pragma unroll
+                for (int si = 0; si < S; ++si) {
+                    const uint4 c4 = q.c[si];
+                    const uint32_t cw = u == 0 ? c4.x : u == 1 ? c4.y : u == 2 ? c4.z : c4.w;
+                    const uint32_t sw = (u & 2) ? q.s[si].y : q.s[si].x;
+                    const float sc = __uint_as_float((u & 1) ? (sw & 0xFFFF0000u) : (sw << 16));
+                    // operand dword t = bf16 pair (16 + c_2t, 16 + c_2t+1): nibble t of each half into the top mantissa bits of 16.0
+                    const uint4 wa = make_uint4(((cw << 3) & 0x00780078u) | 0x41804180u, ((cw >> 1) & 0x00780078u) | 0x41804180u,
+                                                ((cw >> 5) & 0x00780078u) | 0x41804180u, ((cw >> 9) & 0x00780078u) | 0x41804180u);
+                    f32x4 T = mfma16(q.bh[u], wa, T0);
+                    if (NB == 2) T = mfma16(q.bl[NB == 2 ? u : 0], wa, T);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[si][0][r] = fmaf(sc, T[r], acc[si][0][r]);
+                }
+            }
+        };
+        constexpr int DEPTH = (NB == 2 || S >= 4) ? 2 : 3;   // what fits in 128 registers
+        qbatch q0, q1, q2;
+        k_walk<DEPTH>(cnt, q0, q1, q2, issue, consume, [&]() {
+            if (NORM) {
+                const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
+                if (lane < 4) *(float4 *)&ssq_s[wave][0][4 * lane] = s4;
+            }
+            if (PARK && wave == 0) {
+                epi_pre pre;
+                epi_prefetch<EPI>(a, strip0, lane, pre, 0);
+                epi_park<EPI>(&pre_s[lane], pre);
+            }
+        });
+        // acc is (row 4 g + r, feature f) for lane (g, f); the sum below and the epilogues take
+        // (feature 4 g' + r', row j) from lane (g', j): store transposed
+        {
+            float *rf = (float *)&red[wave][0][0][0];
+            const int g = lane >> 4, f = lane & 15;
 #pragma unroll
             for (int si = 0; si < S; ++si)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const char *p = Aq + (strip0 + si < a.nstrips ? (size_t)si * qstrip : 0) + (size_t)((t >> 2) + h) * PV_Q4_BATCH;
-                    qc[si][h] = *(const uint4 *)(p + lane * 16);
-                    qs[si][h][0] = *(const uint4 *)(p + 1024 + (lane >> 4) * 32);
-                    qs[si][h][1] = *(const uint4 *)(p + 1024 + (lane >> 4) * 32 + 16);
-                }
+                for (int r = 0; r < 4; ++r) rf[si * 256 + ((f >> 2) * 16 + 4 * g + r) * 4 + (f & 3)] = acc[si][0][r];
         }
+    } else if constexpr (DP > 1) {
+        // Few workgroups per CU (a GEMM with about as many strips as the machine has CUs): the
+        // bytes in flight come from depth per wave instead of from resident waves.
+        static_assert(NB == 1 && CT == 1 && S == 1, "deep variant: packed rows, one strip");
+        struct wbatch { uint4 w[U], x[U]; };
+        const int wv = __builtin_amdgcn_readfirstlane(wave);
+        int first, cnt, bstride;
+        if (a.interleave) { first = wv; bstride = NW; cnt = wv < nbat ? (nbat - wv + NW - 1) / NW : 0; }
+        else { const int per = (nbat + NW - 1) / NW; first = min(nbat, wv * per); cnt = min(nbat, first + per) - first; bstride = 1; }
+        auto issue = [&](wbatch &q, int k) {
+            const size_t o = (size_t)(first + k * bstride) * U * 64;
+#pragma unroll
+            for (int u = 0; u < U; ++u) { q.w[u] = A[o + u * 64]; q.x[u] = B[o + u * 64]; }
+            asm volatile("" ::: "memory");
+        };
+        auto consume = [&](const wbatch &q) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[0][0] = mfma16(q.w[u], q.x[u], acc[0][0]);
+        };
+        wbatch q0, q1, q2;
+        k_walk<DP>(cnt, q0, q1, q2, issue, consume, [&]() {
+            if (NORM) {
+                const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
+                if (lane < 4) *(float4 *)&ssq_s[wave][0][4 * lane] = s4;
+            }
+            if (PARK && wave == 0) {
+                epi_pre pre;
+                epi_prefetch<EPI>(a, strip0, lane, pre, 0);
+                epi_park<EPI>(&pre_s[lane], pre);
+            }
+        });
+        if (wave == NW - 1) {
+            for (int t = nbat * U; t < KT; ++t) acc[0][0] = mfma16(A[(size_t)t * 64], B[(size_t)t * 64], acc[0][0]);
+        }
+    } else {
+    uint4 ra[S][U], rb[CT][U], rc[CT][U];
+    auto load_batch = [&](int t) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const size_t o = (size_t)(t + u) * 64;
-            if (WB == 16) {
 #pragma unroll
-                for (int si = 0; si < S; ++si) ra[si][u] = A[so[si] + o];
-            }
+            for (int si = 0; si < S; ++si) ra[si][u] = A[so[si] + o];
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 rb[ct][u] = B[(size_t)(2 * ct) * arr + o];
@@ -275,21 +400,6 @@ k_gemm(const gemm_args a)
         }
     };
     auto use_batch = [&]() {
-        if (WB == 4) {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                f32x4 T0 = {0.f, 0.f, 0.f, 0.f};
-                T0 = mfma16(neg24, rb[0][u], T0);
-                if (NB == 2) T0 = mfma16(neg24, rc[0][u], T0);
-#pragma unroll
-                for (int si = 0; si < S; ++si) {
-                    const uint4 c4 = qc[si][u >> 2], sq = qs[si][u >> 2][(u >> 1) & 1];
-                    const uint32_t cw = (u & 3) == 0 ? c4.x : (u & 3) == 1 ? c4.y : (u & 3) == 2 ? c4.z : c4.w;
-                    q4_tile(si, cw, (u & 1) ? sq.z : sq.x, (u & 1) ? sq.w : sq.y, rb[0][u], rc[0][u], T0);
-                }
-            }
-            return;
-        }
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -323,27 +433,8 @@ k_gemm(const gemm_args a)
         load_batch(b * U);
         use_batch();
     }
-    if (WB == 4 && wave == NW - 1 && nbat * U < KT) {    // an odd batch of 4 tiles is left over
-        const int t = nbat * U;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const size_t o = (size_t)(t + u) * 64;
-            const uint4 bh = B[o];
-            uint4 bl = bh;
-            if (NB == 2) bl = B[arr + o];
-            f32x4 T0 = {0.f, 0.f, 0.f, 0.f};
-            T0 = mfma16(neg24, bh, T0);
-            if (NB == 2) T0 = mfma16(neg24, bl, T0);
-#pragma unroll
-            for (int si = 0; si < S; ++si) {
-                const char *p = Aq + (strip0 + si < a.nstrips ? (size_t)si * qstrip : 0) + (size_t)(t >> 2) * PV_Q4_BATCH;
-                const uint32_t cw = ((const uint32_t *)p)[lane * 4 + u];
-                const uint2 sq = *(const uint2 *)(p + 1024 + (lane >> 4) * 32 + u * 8);
-                q4_tile(si, cw, sq.x, sq.y, bh, bl, T0);
-            }
-        }
-    }
-    if (WB == 16 && wave == NW - 1) {
+    if (wave == NW - 1) {
+
         for (int t = nbat * U; t < KT; ++t) {
             const size_t o = (size_t)t * 64;
 #pragma unroll
@@ -360,13 +451,16 @@ k_gemm(const gemm_args a)
             }
         }
     }
+    }   // WB == 16
 
     // sum the NW K-slices (and the NW shares of the sums of squares) in wave order; wave si runs
     // the epilogue of strip strip0 + si
+    if (WB == 16) {
 #pragma unroll
-    for (int si = 0; si < S; ++si)
+        for (int si = 0; si < S; ++si)
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) red[wave][si][ct][lane] = acc[si][ct];
+            for (int ct = 0; ct < CT; ++ct) red[wave][si][ct][lane] = acc[si][ct];
+    }
     __syncthreads();
     if (wave >= S || strip0 + wave >= a.nstrips) return;
     const int strip = strip0 + wave;
@@ -429,8 +523,10 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
     ga.interleave = g.ktiles > 128;                          // long strips: measured 0.3 % faster per step, short ones 0.3 % slower
     if (m->wbits == 4) {
         if constexpr (CT == 1) {
-            // two strips per workgroup share every activation tile (4 KiB per 2.25 KiB of weights otherwise)
-            if (NB == 1 && strips >= 512 && g.ktiles >= 64) k_gemm<1, 1, 2, EPI, 8, 4><<<(strips + 1) / 2, 512, 0, s>>>(ga);
+            // Several strips per workgroup share every activation tile from registers (one strip:
+            // 4 KiB of tiles from L2 per 1.1 KiB of weights), as many as still leave a workgroup per CU.
+            if (NB == 1 && strips >= 1024 && g.ktiles >= 64) k_gemm<1, 1, 4, EPI, 8, 4><<<(strips + 3) / 4, 512, 0, s>>>(ga);
+            else if (NB == 1 && strips >= 512 && g.ktiles >= 64) k_gemm<1, 1, 2, EPI, 8, 4><<<(strips + 1) / 2, 512, 0, s>>>(ga);
             else if (g.ktiles >= 64) k_gemm<NB, 1, 1, EPI, 16, 4><<<strips, 1024, 0, s>>>(ga);
             else k_gemm<NB, 1, 1, EPI, 8, 4><<<strips, 512, 0, s>>>(ga);
         } else {
@@ -448,7 +544,9 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         // waves per workgroup (= K split): 16 where K can feed them (measured rarely slower), 8 for
         // a short K and for the many strips of a short-K vocabulary projection (measured faster)
         const bool eight = g.ktiles < 64 || (EPI == EPI_LMHEAD && g.ktiles <= 128);
-        if (eight) k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
+        // At most one or two workgroups per CU: two batches in flight per wave (measured 1 - 4 % on those GEMMs)
+        if (!eight && strips <= 384) k_gemm<NB, CT, 1, EPI, 16, 16, 2><<<strips, 1024, 0, s>>>(ga);
+        else if (eight) k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
         else k_gemm<NB, CT, 1, EPI, 16><<<strips, 1024, 0, s>>>(ga);
     }
     PV_HIP(hipGetLastError());
