@@ -219,8 +219,8 @@ __device__ inline void k_walk(int cnt, Q &q0, Q &q1, Q &q2, FI issue, FC consume
 // ------------------------------------------------------------------------------------------
 //
 // DP > 1 (16-bit weights, packed rows, one strip): the wave keeps DP batches in registers and
-// loads ahead (k_walk), for GEMMs with so few strips that resident waves alone leave too few
-// bytes in flight.
+// loads ahead (k_walk): bytes in flight come from depth per wave rather than from the number of
+// resident waves.
 //
 // WB == 4: the strip is a run of batches of 4-bit codes and bf16 group scales (one scale per
 // output feature and K-tile); the wave walks them with k_walk, two or three batches deep.  A
@@ -351,8 +351,6 @@ k_gemm(const gemm_args a)
                 for (int r = 0; r < 4; ++r) rf[si * 256 + ((f >> 2) * 16 + 4 * g + r) * 4 + (f & 3)] = acc[si][0][r];
         }
     } else if constexpr (DP > 1) {
-        // Few workgroups per CU (a GEMM with about as many strips as the machine has CUs): the
-        // bytes in flight come from depth per wave instead of from resident waves.
         static_assert(NB == 1 && CT == 1 && S == 1, "deep variant: packed rows, one strip");
         struct wbatch { uint4 w[U], x[U]; };
         const int wv = __builtin_amdgcn_readfirstlane(wave);
@@ -541,13 +539,11 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         else if (CT == 1 && g.ktiles >= 64) k_gemm<NB, CT, 1, EPI, 16><<<strips, 1024, 0, s>>>(ga);
         else k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
     } else {
-        // waves per workgroup (= K split): 16 where K can feed them (measured rarely slower), 8 for
-        // a short K and for the many strips of a short-K vocabulary projection (measured faster)
-        const bool eight = g.ktiles < 64 || (EPI == EPI_LMHEAD && g.ktiles <= 128);
-        // At most one or two workgroups per CU: two batches in flight per wave (measured 1 - 4 % on those GEMMs)
-        if (!eight && strips <= 384) k_gemm<NB, CT, 1, EPI, 16, 16, 2><<<strips, 1024, 0, s>>>(ga);
-        else if (eight) k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
-        else k_gemm<NB, CT, 1, EPI, 16><<<strips, 1024, 0, s>>>(ga);
+        // Eight waves, each three batches deep (two workgroups per CU at <= 128 registers): measured
+        // 1 - 8 % faster per GEMM than sixteen waves that load and use one batch at a time; a short K
+        // has too few batches per wave for that
+        if (g.ktiles >= 64) k_gemm<NB, CT, 1, EPI, 8, 16, 3><<<strips, 512, 0, s>>>(ga);
+        else k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
     }
     PV_HIP(hipGetLastError());
     return PV_OK;
