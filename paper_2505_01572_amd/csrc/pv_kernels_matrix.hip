@@ -240,7 +240,7 @@ k_gemm(const gemm_args a)
     static_assert(WB == 16 || (WB == 4 && CT == 1), "4-bit weights: one column tile");
     constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : 4;   // tiles per batch (16-bit weights)
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
-    constexpr bool PARK = (S == 1 && CT == 1);       // epilogue inputs fetched early and parked in LDS
+    constexpr bool PARK = (CT == 1);                 // epilogue inputs fetched early (by the wave that will run the strip's epilogue) and parked in LDS
     const int strip0 = blockIdx.x * S, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int KT = a.ktiles, nbat = KT / U;        // whole batches of U tiles; a ragged rest goes to the last wave
     int b, bend, bstep;
@@ -261,7 +261,7 @@ k_gemm(const gemm_args a)
 
     __shared__ f32x4 red[NW][S][CT][64];
     __shared__ float ssq_s[NW][CT][16];
-    __shared__ epi_pre pre_s[PARK ? 64 : 1];
+    __shared__ epi_pre pre_s[PARK ? S : 1][PARK ? 64 : 1];
 
     // RMSNorm of the input rows: every wave takes its share of the per-strip sums of squares; the
     // loads go out ahead of the weight stream and are folded in behind its first batch
@@ -334,10 +334,10 @@ k_gemm(const gemm_args a)
                 const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][0][4 * lane] = s4;
             }
-            if (PARK && wave == 0) {
+            if (PARK && wave < S) {
                 epi_pre pre;
-                epi_prefetch<EPI>(a, strip0, lane, pre, 0);
-                epi_park<EPI>(&pre_s[lane], pre);
+                epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
+                epi_park<EPI>(&pre_s[wave][lane], pre);
             }
         });
         // acc is (row 4 g + r, feature f) for lane (g, f); the sum below and the epilogues take
@@ -373,10 +373,10 @@ k_gemm(const gemm_args a)
                 const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][0][4 * lane] = s4;
             }
-            if (PARK && wave == 0) {
+            if (PARK && wave < S) {
                 epi_pre pre;
-                epi_prefetch<EPI>(a, strip0, lane, pre, 0);
-                epi_park<EPI>(&pre_s[lane], pre);
+                epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
+                epi_park<EPI>(&pre_s[wave][lane], pre);
             }
         });
         if (wave == NW - 1) {
@@ -420,10 +420,10 @@ k_gemm(const gemm_args a)
                 if (lane < 4) *(float4 *)&ssq_s[wave][ct][4 * lane] = s4;
             }
         }
-        if (PARK && wave == 0) {                    // behind the first batch's loads, ahead of its use
+        if (PARK && wave < S) {                     // behind the first batch's loads, ahead of its use
             epi_pre pre;
-            epi_prefetch<EPI>(a, strip0, lane, pre, 0);
-            epi_park<EPI>(&pre_s[lane], pre);
+            epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
+            epi_park<EPI>(&pre_s[wave][lane], pre);
         }
         if (first) { use_batch(); b += bstep; }
     }
@@ -467,7 +467,7 @@ k_gemm(const gemm_args a)
         f32x4 sum = red[0][wave][ct][lane];
         for (int w = 1; w < NW; ++w) { const f32x4 p = red[w][wave][ct][lane]; sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3]; }
         epi_pre pre;
-        if (PARK) epi_unpark<EPI>(&pre_s[lane], pre);
+        if (PARK) epi_unpark<EPI>(&pre_s[wave][lane], pre);
         else epi_prefetch<EPI>(a, strip, lane, pre, ct);
         if (NORM) {
             float tot = ssq_s[0][ct][lane & 15];
