@@ -238,7 +238,7 @@ k_gemm(const gemm_args a)
     static_assert(NB == 2 || CT == 1, "packed rows come in one tile");
     static_assert(S <= NW, "one epilogue wave per strip");
     static_assert(WB == 16 || (WB == 4 && CT == 1), "4-bit weights: one column tile");
-    constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : 4;   // tiles per batch (16-bit weights)
+    constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : (DP > 1 && S == 2) ? 2 : 4;   // tiles per batch (16-bit weights)
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
     constexpr bool PARK = (CT == 1);                 // epilogue inputs fetched early (by the wave that will run the strip's epilogue) and parked in LDS
     const int strip0 = blockIdx.x * S, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -351,8 +351,8 @@ k_gemm(const gemm_args a)
                 for (int r = 0; r < 4; ++r) rf[si * 256 + ((f >> 2) * 16 + 4 * g + r) * 4 + (f & 3)] = acc[si][0][r];
         }
     } else if constexpr (DP > 1) {
-        static_assert(NB == 1 && CT == 1 && S == 1, "deep variant: packed rows, one strip");
-        struct wbatch { uint4 w[U], x[U]; };
+        static_assert(NB == 1 && CT == 1, "deep variant: packed rows");
+        struct wbatch { uint4 w[S][U], x[U]; };
         const int wv = __builtin_amdgcn_readfirstlane(wave);
         int first, cnt, bstride;
         if (a.interleave) { first = wv; bstride = NW; cnt = wv < nbat ? (nbat - wv + NW - 1) / NW : 0; }
@@ -360,12 +360,18 @@ k_gemm(const gemm_args a)
         auto issue = [&](wbatch &q, int k) {
             const size_t o = (size_t)(first + k * bstride) * U * 64;
 #pragma unroll
-            for (int u = 0; u < U; ++u) { q.w[u] = A[o + u * 64]; q.x[u] = B[o + u * 64]; }
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int si = 0; si < S; ++si) q.w[si][u] = A[so[si] + o + u * 64];
+                q.x[u] = B[o + u * 64];
+            }
             asm volatile("" ::: "memory");
         };
         auto consume = [&](const wbatch &q) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) acc[0][0] = mfma16(q.w[u], q.x[u], acc[0][0]);
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int si = 0; si < S; ++si) acc[si][0] = mfma16(q.w[si][u], q.x[u], acc[si][0]);
         };
         wbatch q0, q1, q2;
         k_walk<DP>(cnt, q0, q1, q2, issue, consume, [&]() {
@@ -380,7 +386,11 @@ k_gemm(const gemm_args a)
             }
         });
         if (wave == NW - 1) {
-            for (int t = nbat * U; t < KT; ++t) acc[0][0] = mfma16(A[(size_t)t * 64], B[(size_t)t * 64], acc[0][0]);
+            for (int t = nbat * U; t < KT; ++t) {
+                const uint4 x = B[(size_t)t * 64];
+#pragma unroll
+                for (int si = 0; si < S; ++si) acc[si][0] = mfma16(A[so[si] + (size_t)t * 64], x, acc[si][0]);
+            }
         }
     } else {
     uint4 ra[S][U], rb[CT][U], rc[CT][U];
@@ -542,7 +552,10 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         // Eight waves, each three batches deep (two workgroups per CU at <= 128 registers): measured
         // 1 - 8 % faster per GEMM than sixteen waves that load and use one batch at a time; a short K
         // has too few batches per wave for that
-        if (g.ktiles >= 64) k_gemm<NB, CT, 1, EPI, 8, 16, 3><<<strips, 512, 0, s>>>(ga);
+        // With strips to spare, two per workgroup share every activation tile (measured: 70B-shaped
+        // gate/up 165 -> 156 us, vocabulary projections 3 - 5 % faster; 8B-shaped gate/up 3 % slower)
+        if (g.ktiles >= 64 && strips >= 1024 && (g.ktiles >= 256 || strips >= 2048)) k_gemm<NB, CT, 2, EPI, 8, 16, 2><<<(strips + 1) / 2, 512, 0, s>>>(ga);
+        else if (g.ktiles >= 64) k_gemm<NB, CT, 1, EPI, 8, 16, 3><<<strips, 512, 0, s>>>(ga);
         else k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
     }
     PV_HIP(hipGetLastError());
