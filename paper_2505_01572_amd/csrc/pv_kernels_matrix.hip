@@ -552,9 +552,13 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         // Eight waves, each three batches deep (two workgroups per CU at <= 128 registers): measured
         // 1 - 8 % faster per GEMM than sixteen waves that load and use one batch at a time; a short K
         // has too few batches per wave for that
-        // With strips to spare, two per workgroup share every activation tile (measured: 70B-shaped
-        // gate/up 165 -> 156 us, vocabulary projections 3 - 5 % faster; 8B-shaped gate/up 3 % slower)
-        if (g.ktiles >= 64 && strips >= 1024 && (g.ktiles >= 256 || strips >= 2048)) k_gemm<NB, CT, 2, EPI, 8, 16, 2><<<(strips + 1) / 2, 512, 0, s>>>(ga);
+        // Two strips per workgroup share every activation tile; taken where the halved number of
+        // workgroups fills the 256 CUs as evenly as the full one (measured, 70B shapes: gate/up
+        // 165 -> 156 us, down 79 -> 75 us, vocabulary projection 97 -> 92 us; where it would leave
+        // CUs unevenly loaded, e.g. 640 or 1792 strips, one strip per workgroup is 3 - 10 % faster)
+        auto fill = [](int wgs) { return (double)wgs / (double)(((wgs + 255) / 256) * 256); };
+        const bool two = strips >= 512 && fill((strips + 1) / 2) >= fill(strips);
+        if (g.ktiles >= 64 && two) k_gemm<NB, CT, 2, EPI, 8, 16, 2><<<(strips + 1) / 2, 512, 0, s>>>(ga);
         else if (g.ktiles >= 64) k_gemm<NB, CT, 1, EPI, 8, 16, 3><<<strips, 512, 0, s>>>(ga);
         else k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
     }
