@@ -20,6 +20,9 @@ MAT_C = pv_inputs.ModelShape("mat_c", 2, 512, 8, 8, 64, 1376, 1008, dtype="bf16"
 # larger K (multiples of 256): 16-wave K split with several tiles per wave, long ragged down-projection slice
 FUSE_A = pv_inputs.ModelShape("fuse_a", 2, 512, 8, 2, 64, 1280, 1008, rope_base=500000.0, dtype="bf16", seed=5454)
 FUSE_B = pv_inputs.ModelShape("fuse_b", 2, 1024, 8, 2, 128, 8448, 2000, rope_base=500000.0, dtype="bf16", seed=5555)
+# K = d_model = 65 tiles: the waves walk their batches several deep and a ragged tile is left over; 512 gate/up strips and
+# 512 vocabulary strips put two strips in a workgroup, 130 down-projection strips one
+DEEP_A = pv_inputs.ModelShape("deep_a", 2, 2080, 8, 2, 128, 4096, 8192, rope_base=500000.0, dtype="bf16", seed=5656)
 
 
 @pytest.fixture(scope="module")
@@ -35,7 +38,7 @@ def _rel_err(pvlib, lg_g, lg_r):
     return (np.abs(lg_g - lg_r) / logit_scale(lg_r)).max()
 
 
-CASES = [(MAT_A, 0), (MAT_B, 0), (MAT_C, 0), (FUSE_A, 0), (FUSE_B, 2)]
+CASES = [(MAT_A, 0), (MAT_B, 0), (MAT_C, 0), (FUSE_A, 0), (FUSE_B, 2), (DEEP_A, 0)]
 
 
 def _check_against_oracle(pvlib, shape, path, max_gamma, prompt_len, gammas, cache_tokens):
@@ -178,9 +181,11 @@ def test_graph_replay_equals_plain_launches(pvlib):
 Q4_A = pv_inputs.ModelShape("q4_a", 3, 128, 8, 2, 32, 384, 512, rope_base=500000.0, dtype="bf16", seed=7171, weight_bits=4)
 Q4_B = pv_inputs.ModelShape("q4_b", 2, 1024, 8, 2, 128, 4224, 2000, rope_base=500000.0, dtype="bf16", seed=7272, weight_bits=4)
 Q4_C = pv_inputs.ModelShape("q4_c", 2, 512, 8, 8, 64, 1408, 1008, dtype="bf16", seed=7373, weight_bits=4)   # MHA, hd 64
+# K = d_model = 17 batches (odd shares per wave); 512 gate/up strips: two per workgroup, 1024 vocabulary strips: four
+Q4_D = pv_inputs.ModelShape("q4_d", 2, 2176, 8, 2, 128, 4096, 16384, rope_base=500000.0, dtype="bf16", seed=7474, weight_bits=4)
 
 
-@pytest.mark.parametrize("shape", [Q4_A, Q4_B, Q4_C], ids=lambda v: v.name)
+@pytest.mark.parametrize("shape", [Q4_A, Q4_B, Q4_C, Q4_D], ids=lambda v: v.name)
 def test_q4_weights_match_oracle(pvlib, shape):
     """The oracle runs the same decoder on the dequantised weights (code - 8) * scale; the library
     streams codes and scales and dequantises inside the matrix-core GEMMs."""
