@@ -114,7 +114,7 @@ __device__ inline void epi_prefetch(const gemm_args &a, int strip, int lane, epi
         if (j < p.rows) {
             if (strip >= a.q_strips) p.phys = a.page_table[p.pos >> a.geom.page_shift];
             if (strip < a.q_strips + a.k_strips) {
-                const int spH = a.geom.head_dim >> 4, tt = strip % spH, e = tt * 8 + 4 * (g & 1);
+                const int spH = a.geom.head_dim >> 4, tt = strip % spH, e = tt * 8 + 4 * (g >> 1);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) p.cs[r] = a.rope[(size_t)j * (a.geom.head_dim >> 1) + e + r];
             }
@@ -172,11 +172,11 @@ __device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 
         const int hd = gm.head_dim, half = hd >> 1, spH = hd >> 4;
         const int tok = p.pos & (gm.page_tokens - 1);
         if (strip < a.q_strips + a.k_strips) {
-            const int h = strip / spH, tt = strip - h * spH, side = g >> 1, e = tt * 8 + 4 * (g & 1);
+            const int h = strip / spH, tt = strip - h * spH, side = g & 1, e = tt * 8 + 4 * (g >> 1);
             float o[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float partner = __shfl_xor(v[r], 32, 64);
+                const float partner = __shfl_xor(v[r], 16, 64);
                 o[r] = side ? v[r] * p.cs[r].x + partner * p.cs[r].y : v[r] * p.cs[r].x - partner * p.cs[r].y;
             }
             if (live) {

@@ -17,8 +17,9 @@
 // RMSNorm is folded in: the producer of x writes (gain * x) as the next operand plus per-strip
 // partial sums of x^2; the consumer multiplies its outputs by rsqrt(mean + eps), which
 // commutes with the contraction.  Rows of W_q/W_k are permuted inside each head so that the two
-// members of a rotary pair sit in the same strip 8 rows apart (lanes l and l^32 of the
-// accumulator); gate and up rows are interleaved the same way for SwiGLU.
+// members of a rotary pair sit in the same half of a strip, 4 rows apart (lanes l and l^16 of
+// the accumulator; either 8-row half of a strip holds 4 whole pairs); gate and up rows are
+// interleaved 8 + 8 per strip for SwiGLU (lanes l and l^32).
 #include <stdio.h>
 #include <stdlib.h>
 #include "pv_gemm_epilogue.h"
@@ -76,7 +77,7 @@ __global__ void k_repack(const uint4 *src, uint4 *dst, int64_t row_begin, int64_
         const int half = head_dim / 2, e = (int)(n % head_dim);
         const int64_t h = n / head_dim;
         const int side = e >= half, p = e - side * half;
-        strip = h * (head_dim / 16) + p / 8; i = (p & 7) + 8 * side;
+        strip = h * (head_dim / 16) + p / 8; i = (p & 3) + 4 * side + 8 * ((p >> 2) & 1);
     } else if (perm == PERM_GATEUP) {
         strip = n / 8; i = (int)(n & 7) + 8 * strip_add;         // strip_add: 0 = gate, 1 = up
     } else {
@@ -114,7 +115,7 @@ __global__ void k_repack_q4(const uint32_t *codes, const uint16_t *scales, char 
         const int half = head_dim / 2, e = (int)(n % head_dim);
         const int64_t h = n / head_dim;
         const int side = e >= half, p = e - side * half;
-        strip = h * (head_dim / 16) + p / 8; i = (p & 7) + 8 * side;
+        strip = h * (head_dim / 16) + p / 8; i = (p & 3) + 4 * side + 8 * ((p >> 2) & 1);
     } else if (perm == PERM_GATEUP) {
         strip = n / 8; i = (int)(n & 7) + 8 * strip_add;
     } else {
