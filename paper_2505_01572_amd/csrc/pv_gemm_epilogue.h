@@ -11,6 +11,7 @@ struct gemm_args {
     const uint4 *xop;           // operand (hi [+ lo array behind it when NB == 2])
     int ktiles;                 // K / 32
     int interleave;             // K assignment of the waves (see k_gemm)
+    int half_base;              // first of the strips that two workgroups share half and half (k_gemm<..., HF>)
     int nstrips;                // strips of this GEMM (a workgroup may own several; the last one may be ragged)
     const pv_dev_state *st;
     // RMSNorm scale of the input rows (QKV, SWIGLU, LMHEAD)

@@ -232,17 +232,24 @@ __device__ inline void k_walk(int cnt, Q &q0, Q &q1, Q &q2, FI issue, FC consume
 // that by the tile's scale and adds.  The product is taken transposed (activation rows x
 // features) so that a lane's four results share one feature, hence one scale; the accumulators
 // are turned back on their way through the LDS reduction.
-template <int NB, int CT, int S, int EPI, int NW, int WB = 16, int DP = 1>
+template <int NB, int CT, int S, int EPI, int NW, int WB = 16, int DP = 1, bool HF = false>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((NB == 1 && S == 1 && WB == 16 && DP == 1) ? 8 : 4)))   // packed bf16 rows, one strip: <= 64 VGPRs, two 16-wave workgroups per CU
 k_gemm(const gemm_args a)
 {
     static_assert(NB == 2 || CT == 1, "packed rows come in one tile");
     static_assert(S <= NW, "one epilogue wave per strip");
     static_assert(WB == 16 || (WB == 4 && CT == 1), "4-bit weights: one column tile");
-    constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : (DP > 1 && S == 2) ? 2 : 4;   // tiles per batch (16-bit weights)
+    static_assert(!HF || (WB == 16 && DP > 1 && S >= 2), "half strips: 16-bit weights, deep walk");
+    constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : (DP > 1 && S >= 2) ? 2 : 4;   // tiles per batch (16-bit weights)
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
     constexpr bool PARK = (CT == 1);                 // epilogue inputs fetched early (by the wave that will run the strip's epilogue) and parked in LDS
-    const int strip0 = blockIdx.x * S, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // HF: the workgroup owns S - 1 whole strips and one 8-feature half of a strip it shares with
+    // its neighbour (strips a.half_base ...), so that a GEMM with (k + 1/2) x 256 strips puts the
+    // same bytes on every CU; the lanes of the other half load nothing for that slot and their
+    // rows of the product are not stored.
+    const int strip0 = blockIdx.x * (HF ? S - 1 : S), wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int hstrip = HF ? a.half_base + ((int)blockIdx.x >> 1) : 0, hsel = blockIdx.x & 1;
+    const bool hlane = !HF || ((lane >> 3) & 1) == hsel;          // lane's feature (lane % 16) lies in the owned half
     const int KT = a.ktiles, nbat = KT / U;        // whole batches of U tiles; a ragged rest goes to the last wave
     int b, bend, bstep;
     if (a.interleave) { b = wave; bend = nbat; bstep = NW; }
@@ -253,7 +260,7 @@ k_gemm(const gemm_args a)
     // a ragged last workgroup re-reads its first strip for the missing ones and drops the result
     size_t so[S];
 #pragma unroll
-    for (int si = 0; si < S; ++si) so[si] = (strip0 + si < a.nstrips) ? (size_t)si * arr : 0;
+    for (int si = 0; si < S; ++si) so[si] = (HF && si == S - 1) ? (size_t)(hstrip - strip0) * arr : (strip0 + si < a.nstrips) ? (size_t)si * arr : 0;
     f32x4 acc[S][CT];
 #pragma unroll
     for (int si = 0; si < S; ++si)
@@ -363,7 +370,10 @@ k_gemm(const gemm_args a)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int si = 0; si < S; ++si) q.w[si][u] = A[so[si] + o + u * 64];
+                for (int si = 0; si < S; ++si) {
+                    if (HF && si == S - 1) { if (hlane) q.w[si][u] = A[so[si] + o + u * 64]; }
+                    else q.w[si][u] = A[so[si] + o + u * 64];
+                }
                 q.x[u] = B[o + u * 64];
             }
             asm volatile("" ::: "memory");
@@ -375,6 +385,11 @@ k_gemm(const gemm_args a)
                 for (int si = 0; si < S; ++si) acc[si][0] = mfma16(q.w[si][u], q.x[u], acc[si][0]);
         };
         wbatch q0, q1, q2;
+        if constexpr (HF) {                          // the lanes that load nothing for the half slot hold zeros
+            const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int u = 0; u < U; ++u) { q0.w[S - 1][u] = z; q1.w[S - 1][u] = z; q2.w[S - 1][u] = z; }
+        }
         k_walk<DP>(cnt, q0, q1, q2, issue, consume, [&]() {
             if (NORM) {
                 const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
@@ -382,7 +397,7 @@ k_gemm(const gemm_args a)
             }
             if (PARK && wave < S) {
                 epi_pre pre;
-                epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
+                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
                 epi_park<EPI>(&pre_s[wave][lane], pre);
             }
         });
@@ -390,7 +405,11 @@ k_gemm(const gemm_args a)
             for (int t = nbat * U; t < KT; ++t) {
                 const uint4 x = B[(size_t)t * 64];
 #pragma unroll
-                for (int si = 0; si < S; ++si) acc[si][0] = mfma16(A[so[si] + (size_t)t * 64], x, acc[si][0]);
+                for (int si = 0; si < S; ++si) {
+                    uint4 w = x;                                  // (any finite value: rows of the other half are dropped)
+                    if (!(HF && si == S - 1) || hlane) w = A[so[si] + (size_t)t * 64];
+                    acc[si][0] = mfma16(w, x, acc[si][0]);
+                }
             }
         }
     } else {
@@ -471,8 +490,9 @@ k_gemm(const gemm_args a)
             for (int ct = 0; ct < CT; ++ct) red[wave][si][ct][lane] = acc[si][ct];
     }
     __syncthreads();
-    if (wave >= S || strip0 + wave >= a.nstrips) return;
-    const int strip = strip0 + wave;
+    const bool hslot = HF && wave == S - 1;
+    if (wave >= S || (!hslot && strip0 + wave >= a.nstrips)) return;
+    const int strip = hslot ? hstrip : strip0 + wave;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
         f32x4 sum = red[0][wave][ct][lane];
@@ -486,6 +506,7 @@ k_gemm(const gemm_args a)
             for (int w = 1; w < NW; ++w) tot += ssq_s[w][ct][lane & 15];
             pre.rj = 1.0f / sqrtf(tot * a.inv_d + a.eps);
         }
+        if (hslot && (lane >> 5) != hsel) pre.rows = 0;           // features 4 (lane / 16) .. + 3 of the other half: nothing to store
         epi_apply<NB, EPI>(a, strip, lane, sum, pre, ct);
     }
 }
@@ -557,6 +578,17 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         // workgroups fills the 256 CUs as evenly as the full one (measured, 70B shapes: gate/up
         // 165 -> 156 us, down 79 -> 75 us, vocabulary projection 97 -> 92 us; where it would leave
         // CUs unevenly loaded, e.g. 640 or 1792 strips, one strip per workgroup is 3 - 10 % faster)
+        // (k + 1/2) x 256 strips (the fused QKV projection of both benchmark shapes): k whole strips
+        // and half of a shared one per workgroup, 256 workgroups
+        if constexpr (EPI == EPI_QKV) {
+            if (g.ktiles >= 64 && strips % 256 == 128 && strips / 256 >= 1 && strips / 256 <= 2) {
+                ga.half_base = (strips / 256) * 256;
+                if (strips / 256 == 1) k_gemm<NB, CT, 2, EPI, 8, 16, 3, true><<<256, 512, 0, s>>>(ga);
+                else k_gemm<NB, CT, 3, EPI, 8, 16, 2, true><<<256, 512, 0, s>>>(ga);
+                PV_HIP(hipGetLastError());
+                return PV_OK;
+            }
+        }
         auto fill = [](int wgs) { return (double)wgs / (double)(((wgs + 255) / 256) * 256); };
         const bool two = strips >= 512 && fill((strips + 1) / 2) >= fill(strips);
         if (g.ktiles >= 64 && two) k_gemm<NB, CT, 2, EPI, 8, 16, 2><<<(strips + 1) / 2, 512, 0, s>>>(ga);
