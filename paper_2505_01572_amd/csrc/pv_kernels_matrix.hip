@@ -239,17 +239,17 @@ k_gemm(const gemm_args a)
     static_assert(NB == 2 || CT == 1, "packed rows come in one tile");
     static_assert(S <= NW, "one epilogue wave per strip");
     static_assert(WB == 16 || (WB == 4 && CT == 1), "4-bit weights: one column tile");
-    static_assert(!HF || (WB == 16 && DP > 1 && S >= 2), "half strips: 16-bit weights, deep walk");
+    static_assert(!HF || ((WB == 4 || DP > 1) && S >= 2 && NB == 1), "half strips: packed rows, walked batches");
     constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : (DP > 1 && S >= 2) ? 2 : 4;   // tiles per batch (16-bit weights)
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
     constexpr bool PARK = (CT == 1);                 // epilogue inputs fetched early (by the wave that will run the strip's epilogue) and parked in LDS
     // HF: the workgroup owns S - 1 whole strips and one 8-feature half of a strip it shares with
     // its neighbour (strips a.half_base ...), so that a GEMM with (k + 1/2) x 256 strips puts the
-    // same bytes on every CU; the lanes of the other half load nothing for that slot and their
-    // rows of the product are not stored.
+    // same bytes on every CU; the lanes of the other half duplicate the owned half's loads for
+    // that slot and their rows of the product are not stored.
     const int strip0 = blockIdx.x * (HF ? S - 1 : S), wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int hstrip = HF ? a.half_base + ((int)blockIdx.x >> 1) : 0, hsel = blockIdx.x & 1;
-    const bool hlane = !HF || ((lane >> 3) & 1) == hsel;          // lane's feature (lane % 16) lies in the owned half
+    const int hl = HF ? ((lane & ~8) | (hsel << 3)) - lane : 0;    // half slot: the lanes of the other half read the owned half's lines again (no further bytes)
     const int KT = a.ktiles, nbat = KT / U;        // whole batches of U tiles; a ragged rest goes to the last wave
     int b, bend, bstep;
     if (a.interleave) { b = wave; bend = nbat; bstep = NW; }
@@ -293,14 +293,15 @@ k_gemm(const gemm_args a)
         else { const int per = (nb4 + NW - 1) / NW; first = min(nb4, wv * per); cnt = min(nb4, first + per) - first; bstride = 1; }
         size_t qo[S];
 #pragma unroll
-        for (int si = 0; si < S; ++si) qo[si] = (strip0 + si < a.nstrips) ? (size_t)si * qstrip : 0;
+        for (int si = 0; si < S; ++si) qo[si] = (HF && si == S - 1) ? (size_t)(hstrip - strip0) * qstrip : (strip0 + si < a.nstrips) ? (size_t)si * qstrip : 0;
         auto issue = [&](qbatch &q, int k) {          // k-th batch of this wave
             const int bt = first + k * bstride;
 #pragma unroll
             for (int si = 0; si < S; ++si) {
                 const char *p = Aq + qo[si] + (size_t)bt * PV_Q4_BATCH;
-                q.c[si] = *(const uint4 *)(p + lane * 16);
-                q.s[si] = *(const uint2 *)(p + 1024 + (lane & 15) * 8);
+                const int ln = lane + ((HF && si == S - 1) ? hl : 0);
+                q.c[si] = *(const uint4 *)(p + ln * 16);
+                q.s[si] = *(const uint2 *)(p + 1024 + (ln & 15) * 8);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -335,7 +336,7 @@ k_gemm(const gemm_args a)
                 }
             }
         };
-        constexpr int DEPTH = (NB == 2 || S >= 4) ? 2 : 3;   // what fits in 128 registers
+        constexpr int DEPTH = (NB == 2 || S >= 3) ? 2 : 3;   // what fits in 128 registers
         qbatch q0, q1, q2;
         k_walk<DEPTH>(cnt, q0, q1, q2, issue, consume, [&]() {
             if (NORM) {
@@ -344,7 +345,7 @@ k_gemm(const gemm_args a)
             }
             if (PARK && wave < S) {
                 epi_pre pre;
-                epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
+                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
                 epi_park<EPI>(&pre_s[wave][lane], pre);
             }
         });
@@ -370,10 +371,7 @@ k_gemm(const gemm_args a)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int si = 0; si < S; ++si) {
-                    if (HF && si == S - 1) { if (hlane) q.w[si][u] = A[so[si] + o + u * 64]; }
-                    else q.w[si][u] = A[so[si] + o + u * 64];
-                }
+                for (int si = 0; si < S; ++si) q.w[si][u] = A[so[si] + o + u * 64 + ((HF && si == S - 1) ? hl : 0)];
                 q.x[u] = B[o + u * 64];
             }
             asm volatile("" ::: "memory");
@@ -385,11 +383,6 @@ k_gemm(const gemm_args a)
                 for (int si = 0; si < S; ++si) acc[si][0] = mfma16(q.w[si][u], q.x[u], acc[si][0]);
         };
         wbatch q0, q1, q2;
-        if constexpr (HF) {                          // the lanes that load nothing for the half slot hold zeros
-            const uint4 z = make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-            for (int u = 0; u < U; ++u) { q0.w[S - 1][u] = z; q1.w[S - 1][u] = z; q2.w[S - 1][u] = z; }
-        }
         k_walk<DP>(cnt, q0, q1, q2, issue, consume, [&]() {
             if (NORM) {
                 const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
@@ -405,11 +398,7 @@ k_gemm(const gemm_args a)
             for (int t = nbat * U; t < KT; ++t) {
                 const uint4 x = B[(size_t)t * 64];
 #pragma unroll
-                for (int si = 0; si < S; ++si) {
-                    uint4 w = x;                                  // (any finite value: rows of the other half are dropped)
-                    if (!(HF && si == S - 1) || hlane) w = A[so[si] + (size_t)t * 64];
-                    acc[si][0] = mfma16(w, x, acc[si][0]);
-                }
+                for (int si = 0; si < S; ++si) acc[si][0] = mfma16(A[so[si] + (size_t)t * 64 + ((HF && si == S - 1) ? hl : 0)], x, acc[si][0]);
             }
         }
     } else {
@@ -555,6 +544,16 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         if constexpr (CT == 1) {
             // Several strips per workgroup share every activation tile from registers (one strip:
             // 4 KiB of tiles from L2 per 1.1 KiB of weights), as many as still leave a workgroup per CU.
+            if constexpr (NB == 1 && EPI == EPI_QKV) {
+                // (k + 1/2) x 256 strips: k whole strips and half of a shared one per workgroup (see the 16-bit launch below)
+                if (g.ktiles >= 64 && strips % 256 == 128 && strips / 256 >= 1 && strips / 256 <= 2) {
+                    ga.half_base = (strips / 256) * 256;
+                    if (strips / 256 == 1) k_gemm<1, 1, 2, EPI, 8, 4, 1, true><<<256, 512, 0, s>>>(ga);
+                    else k_gemm<1, 1, 3, EPI, 8, 4, 1, true><<<256, 512, 0, s>>>(ga);
+                    PV_HIP(hipGetLastError());
+                    return PV_OK;
+                }
+            }
             if (NB == 1 && strips >= 1024 && g.ktiles >= 64) k_gemm<1, 1, 4, EPI, 8, 4><<<(strips + 3) / 4, 512, 0, s>>>(ga);
             else if (NB == 1 && strips >= 512 && g.ktiles >= 64) k_gemm<1, 1, 2, EPI, 8, 4><<<(strips + 1) / 2, 512, 0, s>>>(ga);
             else if (g.ktiles >= 64) k_gemm<NB, 1, 1, EPI, 16, 4><<<strips, 1024, 0, s>>>(ga);
