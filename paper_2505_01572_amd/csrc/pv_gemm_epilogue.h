@@ -208,10 +208,10 @@ __device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 
         float act[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float up = __shfl_xor(v[r], 32, 64);
+            const float up = __shfl_xor(v[r], 16, 64);
             act[r] = v[r] / (1.0f + expf(-v[r])) * up;
         }
-        if (live && g < 2) store_operand4<NB>(a.xop_act, a.F, j, strip * 8 + 4 * g, act);
+        if (live && !(g & 1)) store_operand4<NB>(a.xop_act, a.F, j, strip * 8 + 4 * (g >> 1), act);
     } else {   // EPI_LMHEAD
         const int n = strip * 16 + 4 * g;
         if (live) *(float4 *)(a.logits + (size_t)j * a.vocab + n) = make_float4(v[0], v[1], v[2], v[3]);

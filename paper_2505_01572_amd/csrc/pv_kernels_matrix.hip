@@ -19,7 +19,7 @@
 // commutes with the contraction.  Rows of W_q/W_k are permuted inside each head so that the two
 // members of a rotary pair sit in the same half of a strip, 4 rows apart (lanes l and l^16 of
 // the accumulator; either 8-row half of a strip holds 4 whole pairs); gate and up rows are
-// interleaved 8 + 8 per strip for SwiGLU (lanes l and l^32).
+// interleaved the same way for SwiGLU (4 gate + 4 up features per half strip).
 #include <stdio.h>
 #include <stdlib.h>
 #include "pv_gemm_epilogue.h"
@@ -79,7 +79,7 @@ __global__ void k_repack(const uint4 *src, uint4 *dst, int64_t row_begin, int64_
         const int side = e >= half, p = e - side * half;
         strip = h * (head_dim / 16) + p / 8; i = (p & 3) + 4 * side + 8 * ((p >> 2) & 1);
     } else if (perm == PERM_GATEUP) {
-        strip = n / 8; i = (int)(n & 7) + 8 * strip_add;         // strip_add: 0 = gate, 1 = up
+        strip = n / 8; i = (int)(n & 3) + 4 * strip_add + 8 * (int)((n >> 2) & 1);   // strip_add: 0 = gate, 1 = up
     } else {
         strip = (n / 16) * strip_mul + strip_add; i = (int)(n & 15);
     }
@@ -117,7 +117,7 @@ __global__ void k_repack_q4(const uint32_t *codes, const uint16_t *scales, char 
         const int side = e >= half, p = e - side * half;
         strip = h * (head_dim / 16) + p / 8; i = (p & 3) + 4 * side + 8 * ((p >> 2) & 1);
     } else if (perm == PERM_GATEUP) {
-        strip = n / 8; i = (int)(n & 7) + 8 * strip_add;
+        strip = n / 8; i = (int)(n & 3) + 4 * strip_add + 8 * (int)((n >> 2) & 1);
     } else {
         strip = (n / 16) * strip_mul + strip_add; i = (int)(n & 15);
     }
@@ -544,12 +544,16 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         if constexpr (CT == 1) {
             // Several strips per workgroup share every activation tile from registers (one strip:
             // 4 KiB of tiles from L2 per 1.1 KiB of weights), as many as still leave a workgroup per CU.
-            if constexpr (NB == 1 && EPI == EPI_QKV) {
-                // (k + 1/2) x 256 strips: k whole strips and half of a shared one per workgroup (see the 16-bit launch below)
-                if (g.ktiles >= 64 && strips % 256 == 128 && strips / 256 >= 1 && strips / 256 <= 2) {
-                    ga.half_base = (strips / 256) * 256;
-                    if (strips / 256 == 1) k_gemm<1, 1, 2, EPI, 8, 4, 1, true><<<256, 512, 0, s>>>(ga);
-                    else k_gemm<1, 1, 3, EPI, 8, 4, 1, true><<<256, 512, 0, s>>>(ga);
+            if constexpr (NB == 1 && (EPI == EPI_QKV || EPI == EPI_SWIGLU)) {
+                // strips = (k + 1/2) x G with G a multiple of the 256 CUs: G workgroups of k whole strips and
+                // half of a shared one put the same bytes on every CU (see the 16-bit launch below)
+                for (int k = (strips >= 1024 ? 3 : 2); k >= 1 && g.ktiles >= 64; --k) {
+                    const int G = 2 * strips / (2 * k + 1);
+                    if (2 * strips % (2 * k + 1) != 0 || G % 256 != 0 || G == 0) continue;
+                    ga.half_base = k * G;
+                    if (k == 3) k_gemm<1, 1, 4, EPI, 8, 4, 1, true><<<G, 512, 0, s>>>(ga);
+                    else if (k == 2) k_gemm<1, 1, 3, EPI, 8, 4, 1, true><<<G, 512, 0, s>>>(ga);
+                    else k_gemm<1, 1, 2, EPI, 8, 4, 1, true><<<G, 512, 0, s>>>(ga);
                     PV_HIP(hipGetLastError());
                     return PV_OK;
                 }
