@@ -239,8 +239,8 @@ k_gemm(const gemm_args a)
     static_assert(NB == 2 || CT == 1, "packed rows come in one tile");
     static_assert(S <= NW, "one epilogue wave per strip");
     static_assert(WB == 16 || (WB == 4 && CT == 1), "4-bit weights: one column tile");
-    static_assert(!HF || ((WB == 4 || DP > 1) && S >= 2 && NB == 1), "half strips: packed rows, walked batches");
-    constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : (DP > 1 && S >= 2) ? 2 : 4;   // tiles per batch (16-bit weights)
+    static_assert(!HF || ((WB == 4 || DP > 1) && S >= 2), "half strips: walked batches");
+    constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : (DP > 1 && (S >= 2 || NB == 2)) ? 2 : 4;   // tiles per batch (16-bit weights)
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
     constexpr bool PARK = (CT == 1);                 // epilogue inputs fetched early (by the wave that will run the strip's epilogue) and parked in LDS
     // HF: the workgroup owns S - 1 whole strips and one 8-feature half of a strip it shares with
@@ -360,8 +360,8 @@ k_gemm(const gemm_args a)
                 for (int r = 0; r < 4; ++r) rf[si * 256 + ((f >> 2) * 16 + 4 * g + r) * 4 + (f & 3)] = acc[si][0][r];
         }
     } else if constexpr (DP > 1) {
-        static_assert(NB == 1 && CT == 1, "deep variant: packed rows");
-        struct wbatch { uint4 w[S][U], x[U]; };
+        static_assert(CT == 1, "deep variant: one column tile");
+        struct wbatch { uint4 w[S][U], x[U], xl[NB == 2 ? U : 1]; };     // xl: the lo halves of a 16-row tile
         const int wv = __builtin_amdgcn_readfirstlane(wave);
         int first, cnt, bstride;
         if (a.interleave) { first = wv; bstride = NW; cnt = wv < nbat ? (nbat - wv + NW - 1) / NW : 0; }
@@ -373,6 +373,7 @@ k_gemm(const gemm_args a)
 #pragma unroll
                 for (int si = 0; si < S; ++si) q.w[si][u] = A[so[si] + o + u * 64 + ((HF && si == S - 1) ? hl : 0)];
                 q.x[u] = B[o + u * 64];
+                if (NB == 2) q.xl[NB == 2 ? u : 0] = B[arr + o + u * 64];
             }
             asm volatile("" ::: "memory");
         };
@@ -380,7 +381,10 @@ k_gemm(const gemm_args a)
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int si = 0; si < S; ++si) acc[si][0] = mfma16(q.w[si][u], q.x[u], acc[si][0]);
+                for (int si = 0; si < S; ++si) {
+                    acc[si][0] = mfma16(q.w[si][u], q.x[u], acc[si][0]);
+                    if (NB == 2) acc[si][0] = mfma16(q.w[si][u], q.xl[NB == 2 ? u : 0], acc[si][0]);
+                }
         };
         wbatch q0, q1, q2;
         k_walk<DP>(cnt, q0, q1, q2, issue, consume, [&]() {
@@ -397,8 +401,14 @@ k_gemm(const gemm_args a)
         if (wave == NW - 1) {
             for (int t = nbat * U; t < KT; ++t) {
                 const uint4 x = B[(size_t)t * 64];
+                uint4 xl = x;
+                if (NB == 2) xl = B[arr + (size_t)t * 64];
 #pragma unroll
-                for (int si = 0; si < S; ++si) acc[si][0] = mfma16(A[so[si] + (size_t)t * 64 + ((HF && si == S - 1) ? hl : 0)], x, acc[si][0]);
+                for (int si = 0; si < S; ++si) {
+                    const uint4 w = A[so[si] + (size_t)t * 64 + ((HF && si == S - 1) ? hl : 0)];
+                    acc[si][0] = mfma16(w, x, acc[si][0]);
+                    if (NB == 2) acc[si][0] = mfma16(w, xl, acc[si][0]);
+                }
             }
         }
     } else {
@@ -570,6 +580,15 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         // tiles per batch tile are matched by as many weight tiles (S = 2 or 4); a GEMM with few
         // strips keeps one strip per workgroup and more waves instead.
         constexpr int S = CT == 1 ? 2 : 4, NW = CT == 1 ? 8 : 4;
+        if constexpr (CT == 1) {
+            // one column tile: batches walked several deep, like the packed rows (measured 2 - 3 % per step)
+            if (g.ktiles >= 64) {
+                if (strips >= 512) k_gemm<NB, CT, 2, EPI, 8, 16, 2><<<(strips + 1) / 2, 512, 0, s>>>(ga);
+                else k_gemm<NB, CT, 1, EPI, 8, 16, 3><<<strips, 512, 0, s>>>(ga);
+                PV_HIP(hipGetLastError());
+                return PV_OK;
+            }
+        }
         if (strips >= 256 * S) k_gemm<NB, CT, S, EPI, NW><<<(strips + S - 1) / S, NW * 64, 0, s>>>(ga);
         else if (CT == 1 && g.ktiles >= 64) k_gemm<NB, CT, 1, EPI, 16><<<strips, 1024, 0, s>>>(ga);
         else k_gemm<NB, CT, 1, EPI, 8><<<strips, 512, 0, s>>>(ga);
