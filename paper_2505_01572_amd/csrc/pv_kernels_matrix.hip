@@ -22,6 +22,7 @@
 // interleaved the same way for SwiGLU (4 gate + 4 up features per half strip).
 #include <stdio.h>
 #include <stdlib.h>
+#include <type_traits>
 #include "pv_gemm_epilogue.h"
 
 
@@ -31,10 +32,12 @@ struct mat_ws {                 // carved out of pv_ws::part
     float *ssq0, *ssq1;                         // [column tile][d/16][16] partial sums of x^2
     float *pmax_val; int32_t *pmax_idx;         // [row][vocab/16] per-strip arg-max candidates, row-major
     float *attn_part;                           // attention chunk partials
+    float *tile_part;                           // K-slice partial sums of the wide-block GEMMs (TILE_PART_FLOATS)
 };
 
 static inline size_t xop_elems(int K) { return (size_t)2 * (K / 32) * 512; }   // hi and lo arrays of one 16-row column tile
 static inline int col_tiles(int rows) { return rows <= 16 ? 1 : rows <= 32 ? 2 : 4; }
+static const size_t TILE_PART_FLOATS = (size_t)6 << 20;   // 24 MiB: the K-slicing below stays under it (about 2048 strip x column-tile KiB per 256 workgroups)
 
 static size_t mat_ws_layout(const pv_model *m, int rows_cap, int max_tokens, float *base, mat_ws *w)
 {
@@ -53,6 +56,7 @@ static size_t mat_ws_layout(const pv_model *m, int rows_cap, int max_tokens, flo
     p = take(ctc * (size_t)f.vocab); if (w) w->pmax_val = p;
     p = take(ctc * (size_t)f.vocab); if (w) w->pmax_idx = (int32_t *)p;
     p = take(pv_attn_part_floats(m, rows_cap, max_tokens)); if (w) w->attn_part = p;
+    p = take(ctc >= 2 ? TILE_PART_FLOATS : 0); if (w) w->tile_part = p;
     return off;
 }
 
@@ -510,6 +514,173 @@ k_gemm(const gemm_args a)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Blocks of 17..64 rows (CT = 2 or 4 column tiles of 16 rows, a hi and a lo operand each): 2 CT
+// activation tiles go with every weight tile.  Fetched per wave they outgrow the weight stream
+// in the CU's load path, so here the 8 waves of a workgroup walk the same K range in step, each
+// with its own S strips, and every activation tile is fetched once per workgroup and shared
+// through LDS (two buffers, one barrier per step of U K-tiles).  Weights and activation tiles
+// are loaded D steps ahead into registers; the activation tiles pass through LDS on use.
+// A GEMM with few strips is cut along K as well (blockIdx.y): the slices' partial sums go to
+// `part` and k_tile_finish adds them in slice order and runs the epilogue; with one slice the
+// epilogue runs here.  Workgroups start their K walk at different steps so that they do not
+// all stream from addresses a power of two apart.
+// ------------------------------------------------------------------------------------------
+template <int CT, int S, int EPI>
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4)))
+k_gemm_tile(const gemm_args a, int tps, float4 *part)
+{
+    constexpr int NW = 8, U = 2, D = 4, TPS = U * CT * 2, NLD = TPS / NW;    // TPS activation tiles per step, NLD of them per wave
+    static_assert((NLD == 1 || (NLD == 2 && CT * 2 == NW)) && TPS == NLD * NW, "a wave loads one tile of the step, or two of the same operand array");
+    constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int KT = a.ktiles, t0 = blockIdx.y * tps, t1 = min(KT, t0 + tps);  // this slice's K-tiles (not empty: the launch sees to it)
+    const int nsteps = (t1 - t0 + U - 1) / U;
+    const int rot = (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)nsteps);
+    const size_t arr = (size_t)KT * 64;
+    const int sw = (blockIdx.x * NW + wave) * S;                              // the wave's first strip
+    size_t so[S];                                                             // strips past the end re-read the last one; dropped below
+#pragma unroll
+    for (int si = 0; si < S; ++si) so[si] = (size_t)min(sw + si, a.nstrips - 1) * arr;
+    const uint4 *A = a.W + lane, *B = a.xop + lane;
+    __shared__ uint4 sa[2][TPS][64];
+    __shared__ float ssq_s[NW][CT][16];
+
+    ssq_loads<2> sl[CT];
+    if (NORM && part == nullptr) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+    }
+    f32x4 acc[S][CT];
+#pragma unroll
+    for (int si = 0; si < S; ++si)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) acc[si][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    struct slot { uint4 x0, x1, w[S][U]; };           // one step in flight: the wave's one or two activation tiles, its weight tiles
+    auto first_tile = [&](int step) { int k = step + rot; if (k >= nsteps) k -= nsteps; return t0 + k * U; };
+    auto issue = [&](slot &q, int step) {             // loads of (rotated) step `step`; a tile past the slice's end re-reads its last one
+        const int tb = first_tile(step);
+        {   // tile t of the step: K-tile t / (2 CT) of it, operand array t % (2 CT); the wave takes tiles wave and wave + 8
+            const int u = wave / (CT * 2), r = wave % (CT * 2);
+            q.x0 = B[(size_t)r * arr + (size_t)min(tb + u, t1 - 1) * 64];
+            if (NLD == 2) q.x1 = B[(size_t)r * arr + (size_t)min(tb + u + 1, t1 - 1) * 64];   // CT = 4: 8 more tiles = the next K-tile, same array
+        }
+#pragma unroll
+        for (int si = 0; si < S; ++si)
+#pragma unroll
+            for (int u = 0; u < U; ++u) q.w[si][u] = A[so[si] + (size_t)min(tb + u, t1 - 1) * 64];
+        asm volatile("" ::: "memory");
+    };
+    auto use = [&](const slot &q, int buf, int step) {   // q holds step `step`: share its activation tiles through sa[buf], multiply
+        sa[buf][wave][lane] = make_uint4(q.x0.x, q.x0.y, q.x0.z, q.x0.w);
+        if (NLD == 2) sa[buf][wave + NW][lane] = make_uint4(q.x1.x, q.x1.y, q.x1.z, q.x1.w);
+        __syncthreads();
+        const int tb = first_tile(step);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (tb + u < t1) {
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    const uint4 hi = sa[buf][u * CT * 2 + 2 * ct][lane], lo = sa[buf][u * CT * 2 + 2 * ct + 1][lane];
+#pragma unroll
+                    for (int si = 0; si < S; ++si) {
+                        acc[si][ct] = mfma16(q.w[si][u], hi, acc[si][ct]);
+                        acc[si][ct] = mfma16(q.w[si][u], lo, acc[si][ct]);
+                    }
+                }
+            }
+        }
+    };
+    static_assert(D == 4, "slots are spelled out");
+    slot q0, q1, q2, q3;
+    issue(q0, 0);
+    issue(q1, min(1, nsteps - 1));
+    issue(q2, min(2, nsteps - 1));
+    issue(q3, min(3, nsteps - 1));
+    if (NORM && part == nullptr) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const float4 s4 = ssq_finish(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+            if (lane < 4) *(float4 *)&ssq_s[wave][ct][4 * lane] = s4;
+        }
+    }
+    int s0 = 0;
+    for (; s0 + D <= nsteps; s0 += D) {               // every wave of the workgroup takes the same steps: the barriers match
+        use(q0, 0, s0);     issue(q0, min(s0 + 4, nsteps - 1));
+        use(q1, 1, s0 + 1); issue(q1, min(s0 + 5, nsteps - 1));
+        use(q2, 0, s0 + 2); issue(q2, min(s0 + 6, nsteps - 1));
+        use(q3, 1, s0 + 3); issue(q3, min(s0 + 7, nsteps - 1));
+    }
+    if (s0 < nsteps) use(q0, 0, s0);
+    if (s0 + 1 < nsteps) use(q1, 1, s0 + 1);
+    if (s0 + 2 < nsteps) use(q2, 0, s0 + 2);
+
+    if (part != nullptr) {
+#pragma unroll
+        for (int si = 0; si < S; ++si)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+                if (sw + si < a.nstrips) part[(((size_t)blockIdx.y * a.nstrips + sw + si) * CT + ct) * 64 + lane] = make_float4(acc[si][ct][0], acc[si][ct][1], acc[si][ct][2], acc[si][ct][3]);
+        return;
+    }
+    __syncthreads();                                  // (ssq_s of every wave; also covers a slice of a single step)
+#pragma unroll
+    for (int si = 0; si < S; ++si) {
+        const int strip = sw + si;
+        if (strip >= a.nstrips) continue;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            epi_pre pre;
+            epi_prefetch<EPI>(a, strip, lane, pre, ct);
+            if (NORM) {
+                float tot = ssq_s[0][ct][lane & 15];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) tot += ssq_s[w][ct][lane & 15];
+                pre.rj = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+            }
+            epi_apply<2, EPI>(a, strip, lane, acc[si][ct], pre, ct);
+        }
+    }
+}
+
+// Adds the K-slices' partial sums of k_gemm_tile in slice order and runs the epilogue: one wave
+// per (strip, column tile), the four waves of a workgroup take four strips of column tile
+// blockIdx.y.  At most TILE_MAX_SLICES slices: their loads go out together.
+#define TILE_MAX_SLICES 16
+template <int CT, int EPI>
+__global__ void __launch_bounds__(256)
+k_tile_finish(const gemm_args a, const float4 *part, int slices)
+{
+    constexpr int NW = 4;
+    constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ct = blockIdx.y;
+    const int strip = min((int)blockIdx.x * NW + wave, a.nstrips - 1);           // a wave past the end repeats the last strip's loads and stores nothing
+    const bool mine = (int)blockIdx.x * NW + wave < a.nstrips;
+    __shared__ float ssq_s[NW][16];
+    ssq_loads<4> sl;
+    if (NORM) ssq_issue(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl);
+    float4 p[TILE_MAX_SLICES];
+#pragma unroll
+    for (int y = 0; y < TILE_MAX_SLICES; ++y) p[y] = part[(((size_t)(y < slices ? y : 0) * a.nstrips + strip) * CT + ct) * 64 + lane];
+    epi_pre pre;
+    epi_prefetch<EPI>(a, strip, lane, pre, ct);
+    if (NORM) {
+        const float4 s4 = ssq_finish(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl);
+        if (lane < 4) *(float4 *)&ssq_s[wave][4 * lane] = s4;
+        __syncthreads();
+        float tot = ssq_s[0][lane & 15];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) tot += ssq_s[w][lane & 15];
+        pre.rj = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+    }
+    float4 v = p[0];
+#pragma unroll
+    for (int y = 1; y < TILE_MAX_SLICES; ++y)
+        if (y < slices) { v.x += p[y].x; v.y += p[y].y; v.z += p[y].z; v.w += p[y].w; }
+    if (mine) epi_apply<2, EPI>(a, strip, lane, (f32x4){v.x, v.y, v.z, v.w}, pre, ct);   // (wave-uniform; no barrier inside)
+}
+
 // arg-max over the per-strip candidates of one row
 __global__ void __launch_bounds__(256)
 k_argmax_parts(pv_dev_state *st, const float *pv, const int32_t *pi, int strips)
@@ -580,6 +751,22 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         // tiles per batch tile are matched by as many weight tiles (S = 2 or 4); a GEMM with few
         // strips keeps one strip per workgroup and more waves instead.
         constexpr int S = CT == 1 ? 2 : 4, NW = CT == 1 ? 8 : 4;
+        if constexpr (CT >= 2) {
+            // activation tiles shared through LDS; few strips: cut along K so that about 256 workgroups run
+            if (g.ktiles >= 16) {
+                const int ngroups = (strips + 7) / 8;
+                int slices = ngroups >= 192 ? 1 : min(TILE_MAX_SLICES, (256 + ngroups - 1) / ngroups);
+                int tps = (g.ktiles + slices - 1) / slices;
+                tps = max(8, (tps + 1) & ~1);                        // whole steps, at least four per slice
+                slices = (g.ktiles + tps - 1) / tps;
+                while (slices > 1 && (size_t)slices * strips * CT * 256 > TILE_PART_FLOATS) { tps += 2; slices = (g.ktiles + tps - 1) / tps; }
+                float4 *part = slices > 1 ? (float4 *)g.tile_part : nullptr;
+                k_gemm_tile<CT, 1, EPI><<<dim3(ngroups, slices), 512, 0, s>>>(ga, tps, part);
+                PV_HIP(hipGetLastError());
+                if (slices > 1) { k_tile_finish<CT, EPI><<<dim3((strips + 3) / 4, CT), 256, 0, s>>>(ga, part, slices); PV_HIP(hipGetLastError()); }
+                return PV_OK;
+            }
+        }
         if constexpr (CT == 1) {
             // one column tile: batches walked several deep, like the packed rows (measured 2 - 3 % per step)
             if (g.ktiles >= 64) {
@@ -643,6 +830,7 @@ static int run_block(pv_cache *c, hipStream_t s)
     g.n_q_heads = f.n_q_heads; g.q_strips = qd / 16; g.k_strips = kvd / 16;
     g.x = c->ws.x; g.d = d; g.xop_act = mw.xop_d; g.F = F;
     g.logits = c->ws.logits; g.pmax_val = mw.pmax_val; g.pmax_idx = mw.pmax_idx; g.vocab = f.vocab;
+    g.tile_part = mw.tile_part;
 
     for (int l = 0; l < f.n_layers; ++l) {
         // fused QKV projection: RMSNorm scale, rotary embedding, KV append
