@@ -83,6 +83,17 @@ def test_full_prefix_two_layers(pvlib, name, T0):
     assert np.abs(ge - re_).max() <= 2.0 ** -7 * np.abs(re_).max()
 
 
+@pytest.mark.parametrize("name,T0", [("8b", 300), ("70b", 200)])
+def test_full_width_wide_blocks_two_layers(pvlib, name, T0):
+    """Blocks of 17..64 rows at full width (shared-tile GEMM: K cut over workgroups for the
+    projections with few strips, one slice for gate/up and the vocabulary projection); the prompt
+    goes in as 64-row chunks plus a ragged rest."""
+    from gpu_helpers import paired_models
+    shape = CONFIGS[name].replace(n_layers=2)
+    gm, rm = paired_models(shape, max_gamma=64)
+    _compare_steps(pvlib, gm, rm, shape, T0, (64, 17, 32, 8, 40), 0.7, 7200)
+
+
 @pytest.mark.parametrize("name,T0", [("8b", 96), ("7b", 96)])
 def test_full_depth_short_prefix(pvlib, name, T0):
     """Every layer at full width; the prompt is cut to what the oracle prefills in seconds."""
