@@ -33,7 +33,7 @@ HBM_PEAK_GBPS = 8000.0
 # commands: profiles/hbm_traffic_pmc_8b_70b.txt.  Keyed by (workload, gamma bucket, kernel).
 MEASURED_TRAFFIC = {
     ("8b", "rows<=8", "gateup"): 236423261 + 171176,
-    ("70b", "rows<=8", "gateup"): 955218404 + 342352,
+    ("70b", "rows<=8", "gateup"): 949226090 + 391260,
 }
 
 DEFAULTS = {  # workload -> (prefix, gamma, alpha)
