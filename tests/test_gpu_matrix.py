@@ -89,6 +89,33 @@ def test_wide_blocks_match_oracle(pvlib, shape):
     _check_against_oracle(pvlib, shape, 0, 64, 100, (32, 17, 64, 8, 40, 1, 33), 320)
 
 
+LONG_A = pv_inputs.ModelShape("long_a", 1, 128, 8, 2, 32, 352, 512, rope_base=500000.0, dtype="bf16", seed=5757)
+
+
+def test_long_prefix_many_attention_chunks(pvlib):
+    """8300 cached positions: with 32 query rows per kv head (gamma 8, group 4) attention makes 65
+    chunks of 128 keys, more than the lanes of a wave, and the chunk merge takes its general path;
+    with 16 rows (gamma 4) it makes 33 chunks of 256 keys and takes the wave-shuffle path."""
+    from gpu_helpers import gpu_model
+    gm = gpu_model(LONG_A, gains="perturbed", kernel_path=0, max_gamma=64)
+    rm = ref_model(LONG_A, gains="perturbed")
+    T0 = 8300
+    prompt = pv_inputs.uniform_tokens(63, T0, LONG_A.vocab)
+    gc, rc = pvlib.Cache(gm, T0 + 64), ref.RefCache(rm, T0 + 64, ref.KV_BF16)
+    gc.prefill(prompt)
+    last = rc.prefill(prompt)
+    assert _rel_err(pvlib, gc.debug_logits()[-1:], last[None]) < 2e-3
+    for step, gamma in enumerate((8, 4, 1, 16)):
+        T = len(rc)
+        d = pv_inputs.uniform_tokens(64 + step, gamma, LONG_A.vocab)
+        if rc.pending >= 0:
+            d[0] = rc.pending
+        n_r, t_r, pred_r, lg_r = rc.verify(T, d, want_logits=True)
+        gc.verify(T, d)
+        assert _rel_err(pvlib, gc.debug_logits(), lg_r) < 2e-3, f"gamma {gamma}"
+        gc.rollback(T); rc.rollback(T)          # every block on the same 8300-token prefix
+
+
 def test_matrix_and_vector_paths_agree(pvlib):
     from gpu_helpers import gpu_model
     ma = gpu_model(MAT_A, gains="perturbed")
