@@ -1,12 +1,14 @@
 // Matrix-core kernel family for bf16 models.
 //
-// Skinny GEMMs y[rows<=16][N] = x[rows][K] W^T stream W once from HBM.  W is stored pre-tiled
+// Skinny GEMMs y[rows<=64][N] = x[rows][K] W^T stream W once from HBM.  W is stored pre-tiled
 // in MFMA operand order: strips of 16 output features, each strip a run of K/32 tiles of
 // 16x32 bf16 (1 KiB), a tile laid out [lane 0..63][8 bf16] so that one 16-byte load per lane
-// is exactly the A operand of v_mfma_f32_16x16x32_bf16.  A workgroup owns one strip: its 8
-// wavefronts split K, accumulate in fp32, and are summed in wave order through LDS, so the
-// owner sees complete outputs and the whole epilogue (RMSNorm scale, rotary embedding + KV
-// append, SwiGLU, residual add, vocabulary arg-max) is fused into the GEMM.
+// is exactly the A operand of v_mfma_f32_16x16x32_bf16.  Up to 16 rows (k_gemm): a workgroup
+// owns one or a few strips, its wavefronts split K, accumulate in fp32, and are summed in wave
+// order through LDS, so the owner sees complete outputs and the whole epilogue (RMSNorm scale,
+// rotary embedding + KV append, SwiGLU, residual add, vocabulary arg-max) is fused into the
+// GEMM.  17..64 rows (k_gemm_tile): the waves of a workgroup own different strips, walk K
+// together and share the activation tiles through LDS.
 //
 // Activations enter as the B operand.  To keep fp32-grade accuracy with bf16 matrix cores an
 // activation a is carried as two bf16 numbers hi = bf16(a), lo = bf16(a - hi) (16 mantissa
@@ -213,19 +215,19 @@ __device__ inline void k_walk(int cnt, Q &q0, Q &q1, Q &q2, FI issue, FC consume
 // The streaming GEMM: a workgroup owns S adjacent strips, its NW waves split K in batches of U
 // tiles.
 //
-// Rows: NB == 1 packs up to 8 rows (hi and lo halves in one operand; CT == 1, S == 1).  NB == 2
-// takes the rows in CT column tiles of 16, each with a hi and a lo operand, and keeps S x CT
+// Rows: NB == 1 packs up to 8 rows (hi and lo halves in one operand; CT == 1).  NB == 2 takes
+// the rows in CT column tiles of 16, each with a hi and a lo operand, and keeps S x CT
 // accumulators: every operand tile fetched from L2 is used for S strips from registers, which
 // keeps the operand traffic (2 CT tiles per batch tile) from outgrowing the weight stream
-// (S tiles) in the CU's load path.
+// (S tiles) in the CU's load path.  (CT > 1 is only used for a K too short for k_gemm_tile.)
 //
 // K assignment: contiguous runs of batches per wave, or batch b to wave b % NW (the workgroup
 // then reads its strips as advancing windows).
 // ------------------------------------------------------------------------------------------
 //
-// DP > 1 (16-bit weights, packed rows, one strip): the wave keeps DP batches in registers and
-// loads ahead (k_walk): bytes in flight come from depth per wave rather than from the number of
-// resident waves.
+// DP > 1 (16-bit weights, one column tile): the wave keeps DP batches in registers and loads
+// ahead (k_walk): bytes in flight come from depth per wave rather than from the number of
+// resident waves.  HF: the last of the S strips is an 8-feature half (see below).
 //
 // WB == 4: the strip is a run of batches of 4-bit codes and bf16 group scales (one scale per
 // output feature and K-tile); the wave walks them with k_walk, two or three batches deep.  A
