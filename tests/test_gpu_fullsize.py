@@ -70,7 +70,7 @@ def _compare_steps(pvlib, gm, rm, shape, T0, gammas, alpha, seed, expect=5e-3):
     return gc, rc
 
 
-@pytest.mark.parametrize("name,T0", [("8b", 2048), ("7b", 512), ("70b", 1024), ("1b", 1024), ("70b_q4", 1024)])
+@pytest.mark.parametrize("name,T0", [("8b", 2048), ("7b", 512), ("70b", 1024), ("1b", 1024), ("70b_q4", 1024), ("8b_q4", 512)])
 def test_full_prefix_two_layers(pvlib, name, T0):
     """Full width, full prompt length, gamma in {1,4,8,16}; first two layers (+ final norm and LM head)."""
     from gpu_helpers import paired_models
