@@ -140,7 +140,8 @@ int pv_cache_set_page_table(pv_cache *c, const int32_t *phys_pages, int32_t n_pa
 /* ---- the step ---- */
 
 /*
- * Append n prompt tokens (host array), all accepted, in chunks of at most max_gamma rows.
+ * Append n prompt tokens (host array), all accepted, in chunks of at most max_gamma rows
+ * (matrix path with 16-bit weights: of up to 64 rows, whatever max_gamma is).
  * Afterwards length += n and pending = the stage's greedy token after the prompt.
  * Synchronises hip_stream before returning.
  */

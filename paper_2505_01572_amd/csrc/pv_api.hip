@@ -264,7 +264,14 @@ static size_t layout_ws(const pv_model *m, int rows_cap, int n_pages, pv_ws *w, 
     return off;
 }
 
-static inline int rows_cap_of(const pv_model *m) { return (m->cfg.max_gamma + PV_ROW_PAD - 1) / PV_ROW_PAD * PV_ROW_PAD; }
+// Rows per prefill chunk: the widest block the kernels of this model have (the matrix path with
+// 16-bit weights: PV_MAX_ROWS whatever max_gamma is; a prompt then needs a quarter of the passes
+// over the weights that 16-row chunks would).  The workspace is sized for it.
+static inline int prefill_rows_of(const pv_model *m)
+{
+    return (m->path >= PV_PATH_MATRIX && m->wbits != 4 && m->cfg.max_gamma < PV_MAX_ROWS) ? PV_MAX_ROWS : m->cfg.max_gamma;
+}
+static inline int rows_cap_of(const pv_model *m) { return (prefill_rows_of(m) + PV_ROW_PAD - 1) / PV_ROW_PAD * PV_ROW_PAD; }
 
 extern "C" int pv_cache_bytes(const pv_model *m, int32_t max_tokens, size_t *page_pool_bytes, size_t *workspace_bytes)
 {
@@ -501,7 +508,7 @@ extern "C" int pv_prefill(pv_cache *c, const int32_t *tokens, int32_t n, void *h
     for (int j = 0; j < n; ++j)
         if (tokens[j] < 0 || tokens[j] >= c->m->cfg.vocab) { pv_set_error("token id %d at position %d outside [0, %d)", tokens[j], j, c->m->cfg.vocab); return PV_ERANGE; }
     hipStream_t s = (hipStream_t)hip_stream;
-    const int chunk = c->m->cfg.max_gamma;
+    const int chunk = prefill_rows_of(c->m);
     for (int off = 0; off < n; off += chunk) {
         const int rows = n - off < chunk ? n - off : chunk;
         const bool last = off + rows >= n;
