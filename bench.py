@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0
 # counter reads for the library's plain copy kernel (--calib-copy) of known size.  Summary and
 # commands: profiles/hbm_traffic_pmc_8b_70b.txt.  Keyed by (workload, gamma bucket, kernel).
 MEASURED_TRAFFIC = {
-    ("8b", "rows<=8", "gateup"): 236423261 + 171176,
-    ("70b", "rows<=8", "gateup"): 949226090 + 391260,
+    ("8b", "rows<=8", "gateup"): 236364522 + 171176,
+    ("70b", "rows<=8", "gateup"): 949250066 + 391260,
 }
 
 DEFAULTS = {  # workload -> (prefix, gamma, alpha)
