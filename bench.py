@@ -53,7 +53,9 @@ def load_model(pv, pv_inputs, shape, max_gamma, kernel_path=0):
     total = shape.n_params()
     # one pinned host buffer, reused for every chunk (no fresh page faults, fast host-to-device copies)
     import torch
-    pinned = torch.empty(m.staging_bytes // 2, dtype=torch.int16, pin_memory=True)
+    widest = max(pv_inputs.tensor_shape(shape, kind)[-1] for kind, _ in pv_inputs.iter_tensors(shape))
+    need = max(m.staging_bytes, 16 * widest * m.np_dtype().itemsize)     # (a model without a staging area still gets 16-row chunks)
+    pinned = torch.empty(need // 2, dtype=torch.int16, pin_memory=True)
     scratch = pinned.numpy().view(m.np_dtype)
     last = t0
     for kind, layer in pv_inputs.iter_tensors(shape):
