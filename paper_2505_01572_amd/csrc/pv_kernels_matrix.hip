@@ -772,7 +772,17 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
         if constexpr (CT == 1) {
             // one column tile: batches walked several deep, like the packed rows (measured 2 - 3 % per step)
             if (g.ktiles >= 64) {
-                if (strips >= 512) k_gemm<NB, CT, 2, EPI, 8, 16, 2><<<(strips + 1) / 2, 512, 0, s>>>(ga);
+                bool done = false;
+                if constexpr (EPI == EPI_QKV) {       // (k + 1/2) x 256 strips: half strips as for the packed rows
+                    if (strips % 256 == 128 && strips / 256 >= 1 && strips / 256 <= 2) {
+                        ga.half_base = (strips / 256) * 256;
+                        if (strips / 256 == 1) k_gemm<NB, CT, 2, EPI, 8, 16, 3, true><<<256, 512, 0, s>>>(ga);
+                        else k_gemm<NB, CT, 3, EPI, 8, 16, 2, true><<<256, 512, 0, s>>>(ga);
+                        done = true;
+                    }
+                }
+                if (done) ;
+                else if (strips >= 512) k_gemm<NB, CT, 2, EPI, 8, 16, 2><<<(strips + 1) / 2, 512, 0, s>>>(ga);
                 else k_gemm<NB, CT, 1, EPI, 8, 16, 3><<<strips, 512, 0, s>>>(ga);
                 PV_HIP(hipGetLastError());
                 return PV_OK;
