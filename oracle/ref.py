@@ -49,6 +49,8 @@ def load(real="f64"):
         rt = ctypes.c_double if real == "f64" else ctypes.c_float
         lib.ref_silu.argtypes = [rt]
         lib.ref_silu.restype = rt
+        lib.ref_store_round.argtypes = [rt, i32]
+        lib.ref_store_round.restype = rt
         _libs[real] = lib
     return _libs[real]
 
@@ -94,6 +96,11 @@ def rope(v, pos, base, real="f64"):
 
 def silu(z, real="f64"):
     return load(real).ref_silu(z)
+
+
+def store_round(v, kv_store, real="f64"):
+    """What the cache keeps of a key/value element v under storage mode kv_store."""
+    return load(real).ref_store_round(v, kv_store)
 
 
 def dequant_q4(codes, scales):

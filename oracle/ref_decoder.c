@@ -85,6 +85,9 @@ static inline real store_round(real v, int mode)
     return v;
 }
 
+/* the cache's store rounding on its own, so that tests can pin it against a library conversion */
+real ref_store_round(real v, int mode) { return store_round(v, mode); }
+
 static inline real tget(const ref_tensor *t, size_t i)
 {
     return t->dtype == REF_BF16 ? (real)bf16_to_f32(((const uint16_t *)t->data)[i])

@@ -73,7 +73,7 @@ def _check_against_oracle(pvlib, shape, path, max_gamma, prompt_len, gammas, cac
     ge = pv_inputs.bf16_bits_to_f32(gc.export()).astype(np.float64)
     re_ = rc.export()
     print(f"{shape.name}: worst rel logit err {worst:.2e}, KV 1-ulp flips {np.mean(ge != re_):.4f}")
-    assert ge.shape == re_.shape and np.mean(ge != re_) < 0.05     # 1-ulp bf16 flips at rounding boundaries only
+    assert ge.shape == re_.shape and np.mean(ge != re_) < 0.02     # 1-ulp bf16 flips at rounding boundaries only
     assert np.abs(ge - re_).max() <= 2.0 ** -7 * np.abs(re_).max()
 
 

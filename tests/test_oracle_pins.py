@@ -136,6 +136,55 @@ def test_block_equals_sequential_decodes(shape, kv_store):
     assert np.array_equal(a.export(), b.export()) or np.abs(a.export() - b.export()).max() < 1e-12
 
 
+def test_cache_store_rounding_is_round_to_nearest_even():
+    """The oracle rounds K/V on store to the cache's storage type; every bf16 comparison with the
+    GPU rests on that rounding, so it is pinned to torch's own float32 -> bfloat16 conversion
+    (round to nearest, ties to even), bit for bit: hand-picked ties, neighbours of ties, signs,
+    tiny and huge magnitudes, and a large random set.  A truncating store fails on the first tie."""
+    def want_bf16(vals):
+        t = torch.tensor(np.asarray(vals, dtype=np.float64)).to(torch.float32).to(torch.bfloat16)
+        return t.to(torch.float64).numpy()
+
+    def want_f32(vals):
+        return np.asarray(vals, dtype=np.float64).astype(np.float32).astype(np.float64)
+
+    u = 2.0 ** -7                                   # spacing of bfloat16 in [1, 2)
+    ties = [1 + u / 2, 1 + 3 * u / 2, 1 + 5 * u / 2, -(1 + u / 2), -(1 + 3 * u / 2),      # exact halves: to even
+            1 + u / 2 + 2.0 ** -23, 1 + u / 2 - 2.0 ** -23, 1 + 3 * u / 2 - 2.0 ** -23,   # float32 neighbours of a half
+            2 - u / 2, 0.0, -0.0, 1.0, 0.02, -0.02, 3.0e-39, 1e-30, 6.5e4, 3.0e38, float("inf"), -float("inf")]
+    rng = np.random.default_rng(11)
+    rand = np.concatenate([rng.normal(size=20000) * 0.5, rng.normal(size=2000) * 1e-3,
+                           (rng.integers(0, 2 ** 31 - 2 ** 24, size=20000, dtype=np.int64).astype(np.uint32)).view(np.float32).astype(np.float64)])
+    vals = np.concatenate([np.array(ties), rand])
+    got = np.array([ref.store_round(float(v), ref.KV_BF16) for v in vals])
+    assert np.array_equal(got.view(np.uint64), want_bf16(vals).view(np.uint64))
+    assert got[0] == 1.0 and got[1] == 1 + 2 * u and got[2] == 1 + 2 * u       # the ties went to the even neighbour
+    got32 = np.array([ref.store_round(float(v), ref.KV_F32) for v in vals])
+    assert np.array_equal(got32.view(np.uint64), want_f32(vals).view(np.uint64))
+    assert all(ref.store_round(float(v), ref.KV_REAL) == v for v in vals[:200])
+    assert math.isnan(ref.store_round(float("nan"), ref.KV_BF16))
+
+
+@pytest.mark.parametrize("shape", [TINY, GQA], ids=["tiny_mha_f32", "gqa_bf16"])
+def test_stored_kv_is_the_rounded_exact_kv(shape):
+    """Layer 0's keys and values depend on nothing that was stored before, so what a rounding cache
+    exports for layer 0 must be torch's conversion of what the exact cache exports, bit for bit;
+    the layers above see the rounded keys and values and may differ, but only by rounding."""
+    toks = pv_inputs.uniform_tokens(31, 24, shape.vocab)
+    rm = ref_model(shape, gains="perturbed")
+    exact = ref.RefCache(rm, 32, ref.KV_REAL); exact.forward_block(toks, want_logits=False)
+    e = exact.export()
+    for mode, conv in ((ref.KV_BF16, torch.bfloat16), (ref.KV_F32, torch.float32)):
+        c = ref.RefCache(rm, 32, mode); c.forward_block(toks[:10], want_logits=False)
+        for t in toks[10:]:
+            c.decode_one(t)                                   # both forward routines store through the same rounding
+        got = c.export()
+        want0 = torch.tensor(e[0]).to(torch.float32).to(conv).to(torch.float64).numpy()
+        assert np.array_equal(got[0], want0)
+        assert np.array_equal(got, torch.tensor(got).to(torch.float32).to(conv).to(torch.float64).numpy())   # every stored value is representable
+        assert np.abs(got - e).max() < (2.0 ** -6 if mode == ref.KV_BF16 else 1e-6) * np.abs(e).max()
+
+
 def test_f32_oracle_build_close_to_f64():
     m64, m32 = ref_model(TINY, real="f64"), ref_model(TINY, real="f32")
     toks = pv_inputs.uniform_tokens(5, 40, TINY.vocab)
