@@ -43,6 +43,10 @@ def load(real="f64"):
         lib.ref_decode_one.argtypes = [vp, i32, vp]
         lib.ref_forward_block.argtypes = [vp, vp, i32, vp, i32]
         lib.ref_verify.argtypes = [vp, i32, vp, i32, ip, ip, ip, vp, vp]
+        lib.ref_embed_block.argtypes = [vp, vp, i32, vp]
+        lib.ref_layer_block.argtypes = [vp, i32, i32, vp, i32]
+        lib.ref_head_block.argtypes = [vp, vp, i32, vp]
+        lib.ref_cache_set_len.argtypes = [vp, i32]
         lib.ref_rmsnorm.argtypes = [vp, vp, i32, ctypes.c_double, vp]
         lib.ref_linear.argtypes = [vp, i32, vp, i32, i32, vp]
         lib.ref_rope.argtypes = [vp, i32, i32, ctypes.c_double]
@@ -137,6 +141,23 @@ class RefModel:
                                            1 if arr.dtype == np.uint16 else 0)
         assert rc == 0
 
+    def drop_tensor(self, kind, layer):
+        """Forget a borrowed array (the model must not be asked for that tensor again)."""
+        self._keep.pop((kind, layer), None)
+        self.lib.ref_model_set_tensor(self.h, KINDS[kind], layer, None, 0)
+
+    def embed_block(self, tokens):
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        X = np.empty((len(t), self.shape.d_model), dtype=_np_real(self.real))
+        assert self.lib.ref_embed_block(self.h, t.ctypes.data, len(t), X.ctypes.data) == 0
+        return X
+
+    def head_block(self, X):
+        X = np.ascontiguousarray(X, dtype=_np_real(self.real))
+        logits = np.empty((X.shape[0], self.shape.vocab), dtype=X.dtype)
+        assert self.lib.ref_head_block(self.h, X.ctypes.data, X.shape[0], logits.ctypes.data) == 0
+        return logits
+
     def __del__(self):
         if getattr(self, "h", None):
             self.lib.ref_model_free(self.h); self.h = None
@@ -168,6 +189,15 @@ class RefCache:
         assert rc == 0
         self.pending = -1
         return logits
+
+    def layer_block(self, layer, T, X):
+        """Layer `layer` over the rows X (in place) at positions T .. T+len(X)-1; length untouched."""
+        assert X.dtype == self.rt and X.flags.c_contiguous and X.ndim == 2
+        assert self.lib.ref_layer_block(self.h, layer, T, X.ctypes.data, X.shape[0]) == 0
+
+    def set_len(self, n):
+        assert self.lib.ref_cache_set_len(self.h, n) == 0
+        self.pending = -1
 
     def prefill(self, tokens, chunk=64):
         """Append the prompt; sets pending = greedy token after the prompt. Returns last-row logits."""

@@ -278,92 +278,134 @@ int ref_decode_one(ref_cache *c, int token, real *logits)
 
 /* ---------- forward, a block of n rows at once ---------- */
 
+/* X[j][:] = E[tokens[j]][:] */
+int ref_embed_block(const ref_model *m, const int32_t *tokens, int n, real *X)
+{
+    const int d = m->c.d_model;
+    for (int j = 0; j < n; ++j) if (tokens[j] < 0 || tokens[j] >= m->c.vocab) return -1;
+    for (int j = 0; j < n; ++j)
+        for (int i = 0; i < d; ++i) X[(size_t)j * d + i] = tget(&m->global[T_EMBED], (size_t)tokens[j] * d + i);
+    return 0;
+}
+
 /*
- * Appends tokens[0..n) at positions len..len+n-1.  logits (nullable) receives
- * [n][vocab]; if only_last != 0 just the last row's logits are computed and
- * written to logits[0..vocab).  Row j may attend to position p iff p <= len+j,
- * expressed as an explicit n x (len+n) 0/1 mask over the full score matrix.
+ * Decoder layer l over the n rows X[n][d_model] (in place) that sit at positions
+ * T .. T+n-1: their keys and values are written to the cache at those positions,
+ * row j may attend to position p iff p <= T+j, expressed as an explicit
+ * n x (T+n) 0/1 mask over the full score matrix.  Only layer l's tensors need to
+ * be set in the model.  The cache length is not touched: a driver that goes
+ * through a deep model layer by layer (one layer's weights alive at a time) calls
+ * this for every block of rows of a layer before moving to the next layer.
  */
-int ref_forward_block(ref_cache *c, const int32_t *tokens, int n, real *logits, int only_last)
+int ref_layer_block(ref_cache *c, int l, int T, real *X, int n)
 {
     const ref_config *g = &c->m->c;
     const int d = g->d_model, hd = g->head_dim, Hq = g->n_q_heads, Hkv = g->n_kv_heads;
-    const int qd = Hq * hd, kvd = Hkv * hd, F = g->ffn_dim, T = c->len, S = T + n, group = Hq / Hkv;
-    if (n <= 0 || S > c->max_tokens) return -1;
-    for (int j = 0; j < n; ++j) if (tokens[j] < 0 || tokens[j] >= g->vocab) return -1;
+    const int qd = Hq * hd, kvd = Hkv * hd, F = g->ffn_dim, S = T + n, group = Hq / Hkv;
+    if (n <= 0 || T < 0 || S > c->max_tokens || l < 0 || l >= g->n_layers) return -1;
 
-    real *X = (real *)malloc(sizeof(real) * (size_t)n * (size_t)(3 * d + 2 * qd + 2 * F));
-    real *H = X + (size_t)n * d, *XO = H + (size_t)n * d, *Q = XO + (size_t)n * d;
+    real *H = (real *)malloc(sizeof(real) * (size_t)n * (size_t)(2 * d + 2 * qd + 2 * F));
+    real *XO = H + (size_t)n * d, *Q = XO + (size_t)n * d;
     real *O = Q + (size_t)n * qd, *A = O + (size_t)n * qd, *U = A + (size_t)n * F;
     unsigned char *mask = (unsigned char *)malloc((size_t)n * S);
     for (int j = 0; j < n; ++j) for (int p = 0; p < S; ++p) mask[(size_t)j * S + p] = (p <= T + j);
 
-    for (int j = 0; j < n; ++j)
-        for (int i = 0; i < d; ++i) X[(size_t)j * d + i] = tget(&c->m->global[T_EMBED], (size_t)tokens[j] * d + i);
-
-    for (int l = 0; l < g->n_layers; ++l) {
-        real *Kl = kv_at(c, c->K, l, 0), *Vl = kv_at(c, c->V, l, 0);   /* [max_tokens][kvd] */
-        for (int j = 0; j < n; ++j) ref_rmsnorm(X + (size_t)j * d, LT(c->m, l, T_ATTN_NORM), d, g->rms_eps, H + (size_t)j * d);
-        ref_linear(H, n, LT(c->m, l, T_WQ), qd, d, Q);
-        ref_linear(H, n, LT(c->m, l, T_WK), kvd, d, Kl + (size_t)T * kvd);
-        ref_linear(H, n, LT(c->m, l, T_WV), kvd, d, Vl + (size_t)T * kvd);
-        for (int j = 0; j < n; ++j) {
-            for (int hq = 0; hq < Hq; ++hq) ref_rope(Q + (size_t)j * qd + hq * hd, hd, T + j, g->rope_base);
-            for (int hk = 0; hk < Hkv; ++hk) ref_rope(Kl + (size_t)(T + j) * kvd + hk * hd, hd, T + j, g->rope_base);
-            for (int i = 0; i < kvd; ++i) {
-                real *kk = Kl + (size_t)(T + j) * kvd + i, *vv = Vl + (size_t)(T + j) * kvd + i;
-                *kk = store_round(*kk, c->kv_store); *vv = store_round(*vv, c->kv_store);
-            }
+    real *Kl = kv_at(c, c->K, l, 0), *Vl = kv_at(c, c->V, l, 0);   /* [max_tokens][kvd] */
+    for (int j = 0; j < n; ++j) ref_rmsnorm(X + (size_t)j * d, LT(c->m, l, T_ATTN_NORM), d, g->rms_eps, H + (size_t)j * d);
+    ref_linear(H, n, LT(c->m, l, T_WQ), qd, d, Q);
+    ref_linear(H, n, LT(c->m, l, T_WK), kvd, d, Kl + (size_t)T * kvd);
+    ref_linear(H, n, LT(c->m, l, T_WV), kvd, d, Vl + (size_t)T * kvd);
+    for (int j = 0; j < n; ++j) {
+        for (int hq = 0; hq < Hq; ++hq) ref_rope(Q + (size_t)j * qd + hq * hd, hd, T + j, g->rope_base);
+        for (int hk = 0; hk < Hkv; ++hk) ref_rope(Kl + (size_t)(T + j) * kvd + hk * hd, hd, T + j, g->rope_base);
+        for (int i = 0; i < kvd; ++i) {
+            real *kk = Kl + (size_t)(T + j) * kvd + i, *vv = Vl + (size_t)(T + j) * kvd + i;
+            *kk = store_round(*kk, c->kv_store); *vv = store_round(*vv, c->kv_store);
         }
-        const real scale = (real)1 / (real)sqrt((double)hd);
-#pragma omp parallel for schedule(static)
-        for (int hq = 0; hq < Hq; ++hq) {
-            const int hk = hq / group;
-            real *P = (real *)malloc(sizeof(real) * (size_t)n * S);
-            /* scores = Q_h K_h^T / sqrt(hd), masked entries -> -inf */
-            for (int j = 0; j < n; ++j)
-                for (int p = 0; p < S; ++p) {
-                    real s = 0;
-                    const real *qh = Q + (size_t)j * qd + hq * hd, *kh = Kl + (size_t)p * kvd + hk * hd;
-                    for (int e = 0; e < hd; ++e) s += qh[e] * kh[e];
-                    P[(size_t)j * S + p] = mask[(size_t)j * S + p] ? s * scale : -INFINITY;
-                }
-            /* row softmax */
-            for (int j = 0; j < n; ++j) {
-                real *row = P + (size_t)j * S, mx = -INFINITY, den = 0;
-                for (int p = 0; p < S; ++p) if (row[p] > mx) mx = row[p];
-                for (int p = 0; p < S; ++p) { row[p] = (real)exp((double)(row[p] - mx)); den += row[p]; }
-                for (int p = 0; p < S; ++p) row[p] /= den;
-            }
-            /* O_h = P V_h */
-            for (int j = 0; j < n; ++j) {
-                real *oh = O + (size_t)j * qd + hq * hd;
-                for (int e = 0; e < hd; ++e) oh[e] = 0;
-                for (int p = 0; p < S; ++p) {
-                    const real wp = P[(size_t)j * S + p];
-                    const real *vh = Vl + (size_t)p * kvd + hk * hd;
-                    for (int e = 0; e < hd; ++e) oh[e] += wp * vh[e];
-                }
-            }
-            free(P);
-        }
-        ref_linear(O, n, LT(c->m, l, T_WO), d, qd, XO);
-        for (size_t i = 0; i < (size_t)n * d; ++i) X[i] += XO[i];
-
-        for (int j = 0; j < n; ++j) ref_rmsnorm(X + (size_t)j * d, LT(c->m, l, T_FFN_NORM), d, g->rms_eps, H + (size_t)j * d);
-        ref_linear(H, n, LT(c->m, l, T_WG), F, d, A);
-        ref_linear(H, n, LT(c->m, l, T_WU), F, d, U);
-        for (size_t i = 0; i < (size_t)n * F; ++i) A[i] = ref_silu(A[i]) * U[i];
-        ref_linear(A, n, LT(c->m, l, T_WD), d, F, XO);
-        for (size_t i = 0; i < (size_t)n * d; ++i) X[i] += XO[i];
     }
+    const real scale = (real)1 / (real)sqrt((double)hd);
+#pragma omp parallel for schedule(static)
+    for (int hq = 0; hq < Hq; ++hq) {
+        const int hk = hq / group;
+        real *P = (real *)malloc(sizeof(real) * (size_t)n * S);
+        /* scores = Q_h K_h^T / sqrt(hd), masked entries -> -inf */
+        for (int j = 0; j < n; ++j)
+            for (int p = 0; p < S; ++p) {
+                real s = 0;
+                const real *qh = Q + (size_t)j * qd + hq * hd, *kh = Kl + (size_t)p * kvd + hk * hd;
+                for (int e = 0; e < hd; ++e) s += qh[e] * kh[e];
+                P[(size_t)j * S + p] = mask[(size_t)j * S + p] ? s * scale : -INFINITY;
+            }
+        /* row softmax */
+        for (int j = 0; j < n; ++j) {
+            real *row = P + (size_t)j * S, mx = -INFINITY, den = 0;
+            for (int p = 0; p < S; ++p) if (row[p] > mx) mx = row[p];
+            for (int p = 0; p < S; ++p) { row[p] = (real)exp((double)(row[p] - mx)); den += row[p]; }
+            for (int p = 0; p < S; ++p) row[p] /= den;
+        }
+        /* O_h = P V_h */
+        for (int j = 0; j < n; ++j) {
+            real *oh = O + (size_t)j * qd + hq * hd;
+            for (int e = 0; e < hd; ++e) oh[e] = 0;
+            for (int p = 0; p < S; ++p) {
+                const real wp = P[(size_t)j * S + p];
+                const real *vh = Vl + (size_t)p * kvd + hk * hd;
+                for (int e = 0; e < hd; ++e) oh[e] += wp * vh[e];
+            }
+        }
+        free(P);
+    }
+    ref_linear(O, n, LT(c->m, l, T_WO), d, qd, XO);
+    for (size_t i = 0; i < (size_t)n * d; ++i) X[i] += XO[i];
+
+    for (int j = 0; j < n; ++j) ref_rmsnorm(X + (size_t)j * d, LT(c->m, l, T_FFN_NORM), d, g->rms_eps, H + (size_t)j * d);
+    ref_linear(H, n, LT(c->m, l, T_WG), F, d, A);
+    ref_linear(H, n, LT(c->m, l, T_WU), F, d, U);
+    for (size_t i = 0; i < (size_t)n * F; ++i) A[i] = ref_silu(A[i]) * U[i];
+    ref_linear(A, n, LT(c->m, l, T_WD), d, F, XO);
+    for (size_t i = 0; i < (size_t)n * d; ++i) X[i] += XO[i];
+    free(mask); free(H);
+    return 0;
+}
+
+/* logits[j][:] = rmsnorm(X[j]; g_final) W_out^T for the n rows of X */
+int ref_head_block(const ref_model *m, const real *X, int n, real *logits)
+{
+    const int d = m->c.d_model;
+    real *H = (real *)malloc(sizeof(real) * (size_t)n * d);
+    for (int j = 0; j < n; ++j) ref_rmsnorm(X + (size_t)j * d, &m->global[T_FINAL_NORM], d, m->c.rms_eps, H + (size_t)j * d);
+    ref_linear(H, n, &m->global[T_LM_HEAD], m->c.vocab, d, logits);
+    free(H);
+    return 0;
+}
+
+/* set the committed length directly (a layer-by-layer driver commits after the last layer) */
+int ref_cache_set_len(ref_cache *c, int len)
+{
+    if (len < 0 || len > c->max_tokens) return -1;
+    c->len = len;
+    return 0;
+}
+
+/*
+ * Appends tokens[0..n) at positions len..len+n-1.  logits (nullable) receives
+ * [n][vocab]; if only_last != 0 just the last row's logits are computed and
+ * written to logits[0..vocab).
+ */
+int ref_forward_block(ref_cache *c, const int32_t *tokens, int n, real *logits, int only_last)
+{
+    const ref_config *g = &c->m->c;
+    const int d = g->d_model, T = c->len, S = T + n;
+    if (n <= 0 || S > c->max_tokens) return -1;
+    real *X = (real *)malloc(sizeof(real) * (size_t)n * d);
+    if (ref_embed_block(c->m, tokens, n, X) != 0) { free(X); return -1; }
+    for (int l = 0; l < g->n_layers; ++l) ref_layer_block(c, l, T, X, n);
     if (logits) {
         int j0 = only_last ? n - 1 : 0;
-        for (int j = j0; j < n; ++j) ref_rmsnorm(X + (size_t)j * d, &c->m->global[T_FINAL_NORM], d, g->rms_eps, H + (size_t)j * d);
-        ref_linear(H + (size_t)j0 * d, n - j0, &c->m->global[T_LM_HEAD], g->vocab, d, logits);
+        ref_head_block(c->m, X + (size_t)j0 * d, n - j0, logits);
     }
     c->len = S;
-    free(mask); free(X);
+    free(X);
     return 0;
 }
 
