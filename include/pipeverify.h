@@ -41,7 +41,9 @@ typedef enum {
     PV_ESTATE = -2,   /* prefix_len != cache length, weights missing, cache not empty ...  */
     PV_ERANGE = -3,   /* gamma > max_gamma, length + gamma > max_tokens, token id outside  */
     PV_EHIP = -4,     /* a HIP runtime call failed (see pv_last_error)                     */
-    PV_ENOMEM = -5    /* a caller-provided buffer is too small / host allocation failed    */
+    PV_ENOMEM = -5,   /* a caller-provided buffer is too small / host allocation failed    */
+    PV_ENUMERIC = -6  /* a row of the block had no finite logit (NaN weights / activations): the
+                         step committed nothing, length and pending are as before the call     */
 } pv_status;
 
 typedef enum { PV_F32 = 0, PV_BF16 = 1 } pv_dtype;
@@ -110,8 +112,9 @@ void pv_model_destroy(pv_model *m);
 /*
  * Hand over rows [row_begin, row_begin + row_count) of one tensor.  host_rows points at the
  * first of those rows (row-major, storage type of the model).  May be called many times per
- * tensor so that the host never holds a whole model; every row of every tensor must be
- * loaded once before the first pv_prefill / pv_verify.  On the matrix path row_begin and
+ * tensor so that the host never holds a whole model; the chunks of a tensor come in row order
+ * (row_begin = the end of the previous chunk, or 0 to start the tensor over; anything else is
+ * PV_ESTATE) and every tensor must be complete before the first pv_prefill / pv_verify.  On the matrix path row_begin and
  * row_count must be multiples of 16 (except for the norm gains).  The rows are copied to
  * the device and repacked there; the call returns after the copy out of host_rows is done
  * (host_rows may be reused), the repack is ordered on hip_stream.  `layer` is ignored for

@@ -27,6 +27,7 @@ extern "C" const char *pv_strerror(int status)
     case PV_ERANGE: return "value out of range";
     case PV_EHIP: return "HIP runtime error";
     case PV_ENOMEM: return "buffer too small";
+    case PV_ENUMERIC: return "non-finite logits";
     default: return "unknown status";
     }
 }
@@ -150,7 +151,6 @@ extern "C" int pv_model_create(const pv_model_config *cfg, void *d_weights, size
     m->layer = (pv_tensor_ref *)calloc((size_t)cfg->n_layers * PV_T_NKINDS, sizeof(pv_tensor_ref));
     if (!m->layer) { delete m; return PV_ENOMEM; }
     layout_arena(cfg, m);
-    m->inv_freq_uploaded = false;
     int dev = 0; hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
         pv_set_error("no HIP device"); free(m->layer); delete m; return PV_EHIP;
@@ -174,6 +174,15 @@ extern "C" void pv_model_destroy(pv_model *m)
     delete m;
 }
 
+// The rows of a tensor arrive in order: a chunk continues where the last one ended, or starts the
+// tensor over at row 0.  (A row count alone would let overlapping chunks pass for a complete tensor.)
+static int chunk_in_order(const pv_tensor_ref &t, int64_t row_begin)
+{
+    if (row_begin == 0 || row_begin == t.loaded_rows) return PV_OK;
+    pv_set_error("rows of a tensor must be loaded in order: expected row_begin %lld (or 0 to start over), got %lld", (long long)t.loaded_rows, (long long)row_begin);
+    return PV_ESTATE;
+}
+
 extern "C" int pv_load_weights(pv_model *m, int32_t kind, int32_t layer, int64_t row_begin, int64_t row_count,
                                const void *host_rows, void *hip_stream)
 {
@@ -184,6 +193,8 @@ extern "C" int pv_load_weights(pv_model *m, int32_t kind, int32_t layer, int64_t
     pv_tensor_ref &t = global ? m->global[kind] : m->layer[(size_t)layer * PV_T_NKINDS + kind];
     if (row_begin < 0 || row_count <= 0 || row_begin + row_count > t.rows) { pv_set_error("rows [%lld, +%lld) outside tensor of %lld rows", (long long)row_begin, (long long)row_count, (long long)t.rows); return PV_ERANGE; }
     if (m->wbits == 4 && pv_is_q4_kind(kind)) { pv_set_error("tensor kind %d of a 4-bit model is loaded with pv_load_weights_q4", kind); return PV_EINVAL; }
+    int orc = chunk_in_order(t, row_begin);
+    if (orc != PV_OK) return orc;
     hipStream_t s = (hipStream_t)hip_stream;
     const size_t nbytes = (size_t)row_count * t.cols * m->elt;
     const bool tiled = m->path >= PV_PATH_MATRIX && t.rows > 1 && kind != PV_T_EMBED;
@@ -198,7 +209,7 @@ extern "C" int pv_load_weights(pv_model *m, int32_t kind, int32_t layer, int64_t
         if (rc != PV_OK) return rc;
         PV_HIP(hipStreamSynchronize(s));
     }
-    t.loaded_rows += row_count;
+    t.loaded_rows = row_begin + row_count;
     return PV_OK;
 }
 
@@ -213,6 +224,8 @@ extern "C" int pv_load_weights_q4(pv_model *m, int32_t kind, int32_t layer, int6
     pv_tensor_ref &t = global ? m->global[kind] : m->layer[(size_t)layer * PV_T_NKINDS + kind];
     if (row_begin < 0 || row_count <= 0 || row_begin + row_count > t.rows) { pv_set_error("rows [%lld, +%lld) outside tensor of %lld rows", (long long)row_begin, (long long)row_count, (long long)t.rows); return PV_ERANGE; }
     if ((row_begin | row_count) & 15) { pv_set_error("matrix path: row_begin and row_count must be multiples of 16"); return PV_EINVAL; }
+    int orc = chunk_in_order(t, row_begin);
+    if (orc != PV_OK) return orc;
     const size_t cbytes = (size_t)row_count * (t.cols / 2), sbytes = (size_t)row_count * (t.cols / PV_Q4_GROUP) * 2;
     const size_t soff = align_up(cbytes, 256);
     if (soff + sbytes > m->staging_bytes) { pv_set_error("chunk of %zu bytes exceeds staging buffer of %zu", soff + sbytes, m->staging_bytes); return PV_ENOMEM; }
@@ -222,7 +235,7 @@ extern "C" int pv_load_weights_q4(pv_model *m, int32_t kind, int32_t layer, int6
     int rc = pv_mat_repack_q4(m, t, kind, row_begin, row_count, soff, s);
     if (rc != PV_OK) return rc;
     PV_HIP(hipStreamSynchronize(s));
-    t.loaded_rows += row_count;
+    t.loaded_rows = row_begin + row_count;
     return PV_OK;
 }
 
@@ -305,10 +318,13 @@ extern "C" int pv_cache_create(const pv_model *m, void *d_page_pool, size_t page
     c->prof_kind = PV_PROF_NONE; c->prof_pending = 0; c->prof_ev = nullptr; c->prof_ms = 0; c->prof_launches = 0;
     c->use_graphs = true; c->cap_stream = nullptr;
     for (auto &row : c->gexec) for (auto &ge : row) ge = nullptr;
-    if (hipHostMalloc((void **)&c->io, sizeof(pv_host_io), hipHostMallocDefault) != hipSuccess) {
+    if (hipHostMalloc((void **)&c->io, sizeof(pv_host_io), hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) {
         pv_set_error("hipHostMalloc failed"); delete c; return PV_EHIP;
     }
     memset(c->io, 0, sizeof(pv_host_io));
+    if (hipHostGetDevicePointer((void **)&c->d_io, c->io, 0) != hipSuccess) {
+        pv_set_error("hipHostGetDevicePointer failed"); (void)hipHostFree(c->io); delete c; return PV_EHIP;
+    }
     // device state, identity page table; activations zeroed once so padding rows are finite
     // pages start out as zeros so that never-written slots of a page can never hold NaN bit patterns
     hipError_t e = hipMemset(c->d_ws, 0, need_w);
@@ -356,18 +372,13 @@ extern "C" int pv_cache_set_page_table(pv_cache *c, const int32_t *phys_pages, i
 
 // ---- the step ----
 
-// the step's launches on stream s: draft ids in, block forward, acceptance, two results out
+// the step's launches on stream s.  No copy nodes: the first kernel reads the draft ids from the
+// pinned mailbox, the last one writes accepted_len, next_token and the error flag into it; the
+// row count and the mode are kernel arguments (a recorded graph is keyed by them).
 static int record_block(pv_cache *c, int rows, int mode, hipStream_t s)
 {
-    const pv_model *m = c->m;
-    PV_HIP(hipMemcpyAsync(c->ws.state->draft, c->io->draft, sizeof(int32_t) * rows, hipMemcpyHostToDevice, s));
-    int rc = pv_k_set_step(c, rows, mode, s);
-    if (rc != PV_OK) return rc;
-    rc = m->path >= PV_PATH_MATRIX ? pv_mat_run_block(c, s) : pv_vec_run_block(c, s);
-    if (rc != PV_OK) return rc;
-    // accepted, next_token -> mailbox; len/pending follow from them on the host
-    PV_HIP(hipMemcpyAsync(c->io->result, &c->ws.state->accepted, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    return PV_OK;
+    (void)rows; (void)mode;      // read by the kernel families from c->last_rows and c->io->hdr
+    return c->m->path >= PV_PATH_MATRIX ? pv_mat_run_block(c, s) : pv_vec_run_block(c, s);
 }
 
 static int enqueue_block(pv_cache *c, const int32_t *tokens, int rows, int mode, hipStream_t s)
@@ -484,11 +495,14 @@ extern "C" int pv_calib_copy(void *d_dst, const void *d_src, size_t nbytes, void
     return PV_OK;
 }
 
-static void absorb_result(pv_cache *c)
+// after the step's stream has been synchronised: fold the step's results into the host mirror
+static int absorb_result(pv_cache *c)
 {
     prof_collect(c);
     c->len += c->io->result[0];
     c->pending = c->io->result[1];
+    if (c->io->result[2]) { pv_set_error("a row of the block has no finite logit (non-finite weights or activations); nothing was committed"); return PV_ENUMERIC; }
+    return PV_OK;
 }
 
 static int check_ready(const pv_cache *c)
@@ -515,7 +529,7 @@ extern "C" int pv_prefill(pv_cache *c, const int32_t *tokens, int32_t n, void *h
         rc = enqueue_block(c, tokens + off, rows, last ? PV_MODE_PREFILL_LAST : PV_MODE_PREFILL_MID, s);
         if (rc != PV_OK) return rc;
         PV_HIP(hipStreamSynchronize(s));          // the mailbox is reused by the next chunk
-            absorb_result(c);
+        if ((rc = absorb_result(c)) != PV_OK) return rc;
     }
     return PV_OK;
 }
@@ -548,10 +562,10 @@ extern "C" int pv_verify_wait(pv_cache *c, int32_t *accepted_len, int32_t *next_
     if (!c->in_flight) { pv_set_error("no verify in flight"); return PV_ESTATE; }
     c->in_flight = false;
     PV_HIP(hipStreamSynchronize(c->flight_stream));
-    absorb_result(c);
+    const int rc = absorb_result(c);
     *accepted_len = c->io->result[0];
     *next_token = c->io->result[1];
-    return PV_OK;
+    return rc;
 }
 
 extern "C" int pv_verify(pv_cache *c, int32_t prefix_len, const int32_t *draft, int32_t gamma,

@@ -40,6 +40,7 @@ struct attn_args {
     float *part_o;              // [n_kv_heads][MP][max_chunks][32][hd]
     float *part_ml;             // [n_kv_heads][MP][max_chunks][32][2]  (max, sum)
     uint16_t *xop_o;            // merge output: operand of the output projection, K = n_q_heads*hd
+    int n_pages;                // entries of the page table
 };
 
 __device__ inline void split8(const float v[8], uint4 &hi, uint4 &lo)
@@ -66,14 +67,17 @@ __device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int mp, in
     constexpr int KS = HD / 32, ET = HD / 16, OS = HD + 4, NWM = 8 / TILES, CK = 256 / TILES;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, jl = lane & 15, g = lane >> 4;
     const int rt = wave / NWM, kq = wave % NWM;
+    const pv_kv_geom &gm = a.geom;
+    const int sub_shift = gm.page_shift - 4, sub_mask = (1 << sub_shift) - 1;
+    // this wave's 32 keys: two groups of 16.  Which pages they sit in does not depend on the cache
+    // length, so the page-table entries are fetched beside the length, not behind it (an entry past
+    // the table's end is clamped; such keys are past the length as well and never used).
+    const int p0 = c * CK + kq * 32;
+    const int pg0 = min((p0 >> 4) >> sub_shift, a.n_pages - 1), pg1 = min(((p0 >> 4) + 1) >> sub_shift, a.n_pages - 1);
+    const int ph0 = a.page_table[pg0], ph1g = a.page_table[pg1];
     const int len = a.st->len, gamma = a.st->gamma, nkeys = len + gamma;
     if (c * CK >= nkeys) return;
     const int nrows = a.group * gamma;
-    const pv_kv_geom &gm = a.geom;
-    const int sub_shift = gm.page_shift - 4, sub_mask = (1 << sub_shift) - 1;
-
-    // this wave's 32 keys: two groups of 16; a group past the end re-reads the first one (it is masked)
-    const int p0 = c * CK + kq * 32;
     const bool has_keys = p0 < nkeys;
     // this lane's query row: row lane%16 of the wave's 16-row tile
     const int m = mp * 32 + rt * 16 + jl;
@@ -83,8 +87,10 @@ __device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int mp, in
     uint4 kt[2][KS], qh[KS], ql[KS];
     uint2 vt[2][ET];
     if (has_keys) {
-        const int g0 = p0 >> 4, g1 = (p0 + 16 < nkeys) ? g0 + 1 : g0;
-        const int ph0 = a.page_table[g0 >> sub_shift], ph1 = a.page_table[g1 >> sub_shift];
+        // a second group past the end re-reads the first one (it is masked)
+        const bool two = p0 + 16 < nkeys;
+        const int g0 = p0 >> 4, g1 = two ? g0 + 1 : g0;
+        const int ph1 = two ? ph1g : ph0;
         // a dead lane reads row 0 of the first head: its scores are masked below (lim = -1)
         const size_t qoff = ((size_t)j * a.n_q_heads + kvh * a.group + al) * HD + g * 8;
 #pragma unroll

@@ -19,8 +19,7 @@ struct pv_dev_state {
     int32_t gamma;              // rows of the running block
     int32_t mode;
     int32_t accepted, next_token;
-    int32_t error;              // set by kernels on an impossible condition
-    int32_t pad;
+    int32_t pad[2];
     int32_t draft[PV_MAX_ROWS];
     int32_t pred[PV_MAX_ROWS];
 };
@@ -29,7 +28,7 @@ struct pv_dev_state {
 struct pv_host_io {
     int32_t draft[PV_MAX_ROWS];
     int32_t hdr[4];             // len, pending, gamma, mode
-    int32_t result[4];          // accepted, next_token, len, pending
+    int32_t result[4];          // written by the step's last kernel: accepted, next_token, error flag (a row without a finite logit)
 };
 
 struct pv_tensor_ref {
@@ -51,7 +50,6 @@ struct pv_model {
     pv_tensor_ref *layer;       // [n_layers][PV_T_NKINDS]
     pv_tensor_ref global[PV_T_NKINDS];
     size_t inv_freq_off;        // double[head_dim/2]
-    bool inv_freq_uploaded;
     int n_cus;
 };
 
@@ -70,7 +68,8 @@ struct pv_cache {
     char *d_ws; size_t ws_bytes;
     int32_t max_tokens, n_pages, rows_cap;
     pv_ws ws;
-    pv_host_io *io;             // pinned
+    pv_host_io *io;             // pinned host memory, mapped into the device's address space
+    pv_host_io *d_io;           // the same mailbox as the kernels address it
     int32_t len, pending, last_rows;
     int32_t blk_start, blk_rows;   // positions the last block wrote K/V for (blk_rows = 0: none on record)
     bool in_flight; hipStream_t flight_stream;
@@ -141,7 +140,6 @@ size_t pv_mat_part_floats(const pv_model *m, int rows_cap, int max_tokens);
 size_t pv_attn_part_floats(const pv_model *m, int rows_cap, int max_tokens);
 int pv_mat_attention_init(int head_dim);
 int pv_mat_attention(pv_cache *c, int layer, int rows, float *part, uint16_t *xop_o, hipStream_t s);
-int pv_common_export(pv_cache *c, void *d_out, hipStream_t s);   // gathers logical K/V into d_out
 void pv_set_error(const char *fmt, ...);
 
 #define PV_HIP(call)                                                                        \

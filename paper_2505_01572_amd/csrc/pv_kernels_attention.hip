@@ -82,7 +82,7 @@ int pv_mat_attention(pv_cache *c, int layer, int rows, float *part, uint16_t *xo
     const int mp_cap = (a.group * c->rows_cap + 31) / 32;
     a.part_o = part;
     a.part_ml = part + (size_t)f.n_kv_heads * mp_cap * a.max_chunks * 32 * f.head_dim;
-    a.xop_o = xop_o;
+    a.xop_o = xop_o; a.n_pages = c->n_pages;
     const bool nb1 = rows <= 8;
     switch (f.head_dim) {
     case 32: return nb1 ? launch<1, 32>(c, a, rows, s) : launch<2, 32>(c, a, rows, s);

@@ -18,7 +18,7 @@ __device__ inline void pv_st(uint16_t *p, size_t i, float v) { p[i] = pv_f32_to_
 pv_kv_geom pv_geom(const pv_cache *c);
 int pv_k_begin(pv_cache *c, int rows_pad, hipStream_t s);
 int pv_k_rope_append(pv_cache *c, int layer, int rows, hipStream_t s);
-int pv_k_argmax_accept(pv_cache *c, int rows, bool with_argmax, hipStream_t s);
+int pv_k_argmax(pv_cache *c, int rows, hipStream_t s);
+int pv_k_finish(pv_cache *c, int rows, const float *pmax_val, const int32_t *pmax_idx, int strips, hipStream_t s);
 int pv_k_set_state(pv_cache *c, int len, int pending, hipStream_t s);
-int pv_k_set_step(pv_cache *c, int gamma, int mode, hipStream_t s);
 int pv_k_export(pv_cache *c, size_t e0, size_t n, void *d_out, hipStream_t s);

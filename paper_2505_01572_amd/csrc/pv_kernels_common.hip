@@ -8,18 +8,24 @@
 // Angles are formed in double (pos * base^(-2i/head_dim)) so that large positions lose no
 // precision before sin/cos; the table is stored as float2 (cos, sin).
 // ---------------------------------------------------------------------------------------
+// The draft ids are read straight from the cache's pinned host mailbox; block 0 copies them, the
+// row count and the mode into the device state for the kernels that follow.
 template <typename ST>
 __global__ void __launch_bounds__(256)
-k_begin(const pv_dev_state *st, const ST *embed, const double *inv_freq, float *x, float2 *rope, int d, int half)
+k_begin(pv_dev_state *st, const int32_t *mailbox, int gamma, int mode, const ST *embed, const double *inv_freq, float *x, float2 *rope, int d, int half)
 {
-    const int j = blockIdx.x, gamma = st->gamma;
+    const int j = blockIdx.x;
+    if (j == 0) {
+        if ((int)threadIdx.x < gamma) st->draft[threadIdx.x] = mailbox[threadIdx.x];
+        if (threadIdx.x == 0) { st->gamma = gamma; st->mode = mode; }
+    }
     float *xr = x + (size_t)j * d;
     if (j >= gamma) {                        // padding rows: keep them finite
         for (int i = threadIdx.x; i < d; i += 256) xr[i] = 0.f;
         for (int i = threadIdx.x; i < half; i += 256) rope[(size_t)j * half + i] = make_float2(1.f, 0.f);
         return;
     }
-    const ST *e = embed + (size_t)st->draft[j] * d;
+    const ST *e = embed + (size_t)mailbox[j] * d;
     for (int i = threadIdx.x; i < d; i += 256) xr[i] = pv_ld(e, i);
     const double pos = (double)(st->len + j);
     for (int i = threadIdx.x; i < half; i += 256) {
@@ -95,42 +101,89 @@ k_argmax(pv_dev_state *st, const float *logits, int vocab)
         }
         __syncthreads();
     }
-    if (threadIdx.x == 0) st->pred[j] = si[0];
+    if (threadIdx.x == 0) st->pred[j] = (sv[0] == -INFINITY) ? -1 : si[0];     // no finite logit in the row: no arg-max (k_finish reports it)
 }
 
 // ---------------------------------------------------------------------------------------
-// Acceptance rule + in-step rollback (metadata).  One thread.
+// End of a step in one launch: vocabulary arg-max of every row from the per-strip candidates the
+// LM-head epilogue left (matrix path; the vector path has st->pred already), the acceptance rule
+// (Algorithm 1, verify branch: longest draft prefix that equals the stage's own greedy tokens,
+// one correction token) and the in-step rollback (length, pending).  The two results and an
+// error flag go straight to the cache's pinned host mailbox.
+// One workgroup of 16 waves: a row is scanned by 16 / (rows rounded up to a power of two) waves
+// (one wave takes up to four rows when there are more than 16), sixteen candidates per lane in
+// flight; thread 0 applies the rule after the barrier.
 // ---------------------------------------------------------------------------------------
-__global__ void k_accept(pv_dev_state *st)
+__global__ void __launch_bounds__(1024)
+k_finish(pv_dev_state *st, int32_t *result, const float *pv, const int32_t *pi, int strips, int gamma, int mode, int vocab)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    const int gamma = st->gamma;
-    int n, next;
-    if (st->mode == PV_MODE_PREFILL_MID) { n = gamma; next = -1; }
-    else if (st->mode == PV_MODE_PREFILL_LAST) { n = gamma; next = st->pred[gamma - 1]; }
-    else {
-        n = 0;
-        while (n < gamma) {
-            const int expected = (n == 0) ? (st->pending >= 0 ? st->pending : st->draft[0]) : st->pred[n - 1];
-            if (st->draft[n] != expected) break;
-            ++n;
+    __shared__ float wv[16];
+    __shared__ int wi[16];
+    __shared__ int pred_s[PV_MAX_ROWS];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (pv != nullptr && mode != PV_MODE_PREFILL_MID) {
+        int wpr = 16;                                 // waves per row
+        while (wpr > 1 && gamma * wpr > 16) wpr >>= 1;
+        for (int j0 = 0; j0 < gamma; j0 += 16 / wpr) {           // one pass unless there are more than 16 rows
+            const int j = j0 + wave / wpr, part = wave % wpr;
+            float bv = -INFINITY; int bi = 0x7fffffff;
+            if (j < gamma) {
+                const float *rv = pv + (size_t)j * strips; const int32_t *ri = pi + (size_t)j * strips;
+                for (int s0 = part * 64 + lane; s0 < strips; s0 += 64 * wpr * 16) {
+                    float v[16]; int i[16];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) { const int s = s0 + 64 * wpr * u, sc = s < strips ? s : s0; v[u] = rv[sc]; i[u] = ri[sc]; }
+#pragma unroll
+                    for (int u = 0; u < 16; ++u)
+                        if (s0 + 64 * wpr * u < strips && pv_better(v[u], i[u], bv, bi)) { bv = v[u]; bi = i[u]; }
+                }
+            }
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
+                if (pv_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            }
+            if (lane == 0) { wv[wave] = bv; wi[wave] = bi; }
+            __syncthreads();
+            if ((int)threadIdx.x < 16 / wpr && j0 + (int)threadIdx.x < gamma) {
+                float fv = wv[threadIdx.x * wpr]; int fi = wi[threadIdx.x * wpr];
+                for (int w = 1; w < wpr; ++w) if (pv_better(wv[threadIdx.x * wpr + w], wi[threadIdx.x * wpr + w], fv, fi)) { fv = wv[threadIdx.x * wpr + w]; fi = wi[threadIdx.x * wpr + w]; }
+                pred_s[j0 + threadIdx.x] = (fv == -INFINITY) ? -1 : fi;     // no finite logit in the row: no arg-max
+            }
+            __syncthreads();
         }
-        next = (n >= 1) ? st->pred[n - 1] : st->pending;
+    } else {
+        if ((int)threadIdx.x < gamma) pred_s[threadIdx.x] = st->pred[threadIdx.x];
+        __syncthreads();
+    }
+    if (threadIdx.x != 0) return;
+    int n, next, err = 0;
+    if (mode == PV_MODE_PREFILL_MID) { n = gamma; next = -1; }
+    else {
+        // a row without a finite logit has no arg-max: the step reports an error and commits nothing
+        for (int j = 0; j < gamma; ++j) { if (pred_s[j] < 0 || pred_s[j] >= vocab) err = 1; st->pred[j] = pred_s[j]; }
+        if (err) { n = 0; next = st->pending; }
+        else if (mode == PV_MODE_PREFILL_LAST) { n = gamma; next = pred_s[gamma - 1]; }
+        else {
+            n = 0;
+            while (n < gamma) {
+                const int expected = (n == 0) ? (st->pending >= 0 ? st->pending : st->draft[0]) : pred_s[n - 1];
+                if (st->draft[n] != expected) break;
+                ++n;
+            }
+            next = (n >= 1) ? pred_s[n - 1] : st->pending;
+        }
     }
     st->accepted = n;
     st->next_token = next;
     st->pending = next;
     st->len += n;
+    result[0] = n; result[1] = next; result[2] = err;
 }
 
 __global__ void k_set_state(pv_dev_state *st, int len, int pending)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) { st->len = len; st->pending = pending; }
-}
-
-__global__ void k_set_step(pv_dev_state *st, int gamma, int mode)
-{
-    if (threadIdx.x == 0 && blockIdx.x == 0) { st->gamma = gamma; st->mode = mode; }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -172,10 +225,11 @@ int pv_k_begin(pv_cache *c, int rows_pad, hipStream_t s)
     const pv_model *m = c->m;
     const double *inv = (const double *)(m->d_weights + m->inv_freq_off);
     const void *emb = m->d_weights + m->global[PV_T_EMBED].off;
+    const int rows = c->last_rows, mode = c->io->hdr[3];
     if (m->cfg.dtype == PV_BF16)
-        k_begin<uint16_t><<<rows_pad, 256, 0, s>>>(c->ws.state, (const uint16_t *)emb, inv, c->ws.x, c->ws.rope, m->cfg.d_model, m->cfg.head_dim / 2);
+        k_begin<uint16_t><<<rows_pad, 256, 0, s>>>(c->ws.state, c->d_io->draft, rows, mode, (const uint16_t *)emb, inv, c->ws.x, c->ws.rope, m->cfg.d_model, m->cfg.head_dim / 2);
     else
-        k_begin<float><<<rows_pad, 256, 0, s>>>(c->ws.state, (const float *)emb, inv, c->ws.x, c->ws.rope, m->cfg.d_model, m->cfg.head_dim / 2);
+        k_begin<float><<<rows_pad, 256, 0, s>>>(c->ws.state, c->d_io->draft, rows, mode, (const float *)emb, inv, c->ws.x, c->ws.rope, m->cfg.d_model, m->cfg.head_dim / 2);
     PV_HIP(hipGetLastError());
     return PV_OK;
 }
@@ -194,13 +248,17 @@ int pv_k_rope_append(pv_cache *c, int layer, int rows, hipStream_t s)
     return PV_OK;
 }
 
-int pv_k_argmax_accept(pv_cache *c, int rows, bool with_argmax, hipStream_t s)
+int pv_k_argmax(pv_cache *c, int rows, hipStream_t s)
 {
-    if (with_argmax) {
-        k_argmax<<<rows, 1024, 0, s>>>(c->ws.state, c->ws.logits, c->m->cfg.vocab);
-        PV_HIP(hipGetLastError());
-    }
-    k_accept<<<1, 64, 0, s>>>(c->ws.state);
+    k_argmax<<<rows, 1024, 0, s>>>(c->ws.state, c->ws.logits, c->m->cfg.vocab);
+    PV_HIP(hipGetLastError());
+    return PV_OK;
+}
+
+// pmax_val / pmax_idx: per-strip arg-max candidates [rows][strips] (null: st->pred is already filled in)
+int pv_k_finish(pv_cache *c, int rows, const float *pmax_val, const int32_t *pmax_idx, int strips, hipStream_t s)
+{
+    k_finish<<<1, 1024, 0, s>>>(c->ws.state, c->d_io->result, pmax_val, pmax_idx, strips, rows, c->io->hdr[3], c->m->cfg.vocab);
     PV_HIP(hipGetLastError());
     return PV_OK;
 }
@@ -208,13 +266,6 @@ int pv_k_argmax_accept(pv_cache *c, int rows, bool with_argmax, hipStream_t s)
 int pv_k_set_state(pv_cache *c, int len, int pending, hipStream_t s)
 {
     k_set_state<<<1, 64, 0, s>>>(c->ws.state, len, pending);
-    PV_HIP(hipGetLastError());
-    return PV_OK;
-}
-
-int pv_k_set_step(pv_cache *c, int gamma, int mode, hipStream_t s)
-{
-    k_set_step<<<1, 64, 0, s>>>(c->ws.state, gamma, mode);
     PV_HIP(hipGetLastError());
     return PV_OK;
 }

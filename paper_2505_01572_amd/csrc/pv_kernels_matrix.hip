@@ -153,16 +153,22 @@ int pv_mat_repack_q4(const pv_model *m, const pv_tensor_ref &t, int kind, int64_
 }
 
 // Block set-up on the matrix path: embedding rows -> x, first operand, first sum of squares;
-// rotary table for positions len .. len+rows-1.
+// rotary table for positions len .. len+rows-1.  The draft ids come straight from the cache's
+// pinned host mailbox; the first workgroup copies them, the row count and the mode into the
+// device state for the kernels that follow.
 template <int NB>
 __global__ void __launch_bounds__(64)
-k_mat_begin(const pv_dev_state *st, const uint16_t *embed, const uint16_t *gain, const double *inv_freq,
+k_mat_begin(pv_dev_state *st, const int32_t *mailbox, int rows, int mode, const uint16_t *embed, const uint16_t *gain, const double *inv_freq,
             float *x, float *ssq, uint16_t *xop, float2 *rope, int d, int half)
 {
-    const int lane = threadIdx.x, ct = blockIdx.y, j = ct * 16 + (lane & 15), g = lane >> 4, rows = st->gamma, strip = blockIdx.x;
+    const int lane = threadIdx.x, ct = blockIdx.y, j = ct * 16 + (lane & 15), g = lane >> 4, strip = blockIdx.x;
+    if (blockIdx.x == 0 && ct == 0) {
+        for (int i = lane; i < rows; i += 64) st->draft[i] = mailbox[i];
+        if (lane == 0) { st->gamma = rows; st->mode = mode; }
+    }
     float v[4] = {0.f, 0.f, 0.f, 0.f};
     if (j < rows) {
-        const uint16_t *e = embed + (size_t)st->draft[j] * d + strip * 16 + 4 * g;
+        const uint16_t *e = embed + (size_t)mailbox[j] * d + strip * 16 + 4 * g;
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] = pv_bf16_to_f32(e[r]);
     }
@@ -683,36 +689,6 @@ k_tile_finish(const gemm_args a, const float4 *part, int slices)
     if (mine) epi_apply<2, EPI>(a, strip, lane, (f32x4){v.x, v.y, v.z, v.w}, pre, ct);   // (wave-uniform; no barrier inside)
 }
 
-// arg-max over the per-strip candidates of one row
-__global__ void __launch_bounds__(256)
-k_argmax_parts(pv_dev_state *st, const float *pv, const int32_t *pi, int strips)
-{
-    const int j = blockIdx.x;
-    if (j >= st->gamma) return;
-    float bv = -INFINITY; int bi = 0x7fffffff;
-    const float *rv = pv + (size_t)j * strips; const int32_t *ri = pi + (size_t)j * strips;
-    for (int s0 = threadIdx.x; s0 < strips; s0 += 256 * 8) {          // eight independent loads in flight per thread
-        float v[8]; int i[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) { const int s = s0 + 256 * u, sc = s < strips ? s : s0; v[u] = rv[sc]; i[u] = ri[sc]; }
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (s0 + 256 * u < strips && (v[u] > bv || (v[u] == bv && i[u] < bi))) { bv = v[u]; bi = i[u]; }
-    }
-    __shared__ float sv[256];
-    __shared__ int si[256];
-    sv[threadIdx.x] = bv; si[threadIdx.x] = bi;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) {
-            const float ov = sv[threadIdx.x + s]; const int oi = si[threadIdx.x + s];
-            if (ov > sv[threadIdx.x] || (ov == sv[threadIdx.x] && oi < si[threadIdx.x])) { sv[threadIdx.x] = ov; si[threadIdx.x] = oi; }
-        }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) st->pred[j] = si[0];
-}
-
 // ------------------------------- host side ----------------------------------------
 
 
@@ -842,7 +818,7 @@ static int run_block(pv_cache *c, hipStream_t s)
     const char *Wb = m->d_weights;
     auto gainp = [&](int kind, int l) { return (const uint16_t *)(Wb + pv_tref(m, kind, l).off); };
 
-    k_mat_begin<NB><<<dim3(d / 16, CT), 64, 0, s>>>(c->ws.state, (const uint16_t *)(Wb + m->global[PV_T_EMBED].off), gainp(PV_T_ATTN_NORM, 0),
+    k_mat_begin<NB><<<dim3(d / 16, CT), 64, 0, s>>>(c->ws.state, c->d_io->draft, rows, c->io->hdr[3], (const uint16_t *)(Wb + m->global[PV_T_EMBED].off), gainp(PV_T_ATTN_NORM, 0),
                                            (const double *)(Wb + m->inv_freq_off), c->ws.x, mw.ssq0, mw.xop_a, c->ws.rope, d, hd / 2);
     PV_HIP(hipGetLastError());
 
@@ -893,10 +869,8 @@ static int run_block(pv_cache *c, hipStream_t s)
         if ((prc = pv_prof_mark(c, PV_PROF_LMHEAD, 0, 0, s)) != PV_OK) return prc;
         if ((prc = launch_gemm<NB, CT, EPI_LMHEAD>(m, g, f.vocab / 16, s)) != PV_OK) return prc;
         if ((prc = pv_prof_mark(c, PV_PROF_LMHEAD, 0, 1, s)) != PV_OK) return prc;
-        k_argmax_parts<<<rows, 256, 0, s>>>(c->ws.state, mw.pmax_val, mw.pmax_idx, f.vocab / 16);
-        PV_HIP(hipGetLastError());
     }
-    return pv_k_argmax_accept(c, rows, false, s);
+    return pv_k_finish(c, rows, mw.pmax_val, mw.pmax_idx, f.vocab / 16, s);
 }
 
 int pv_mat_run_block(pv_cache *c, hipStream_t s)

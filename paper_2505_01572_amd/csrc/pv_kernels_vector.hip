@@ -192,17 +192,8 @@ static int run_block(pv_cache *c, hipStream_t s)
         if ((rc = launch_linear<ST>(m, m->global[PV_T_LM_HEAD], w.h, nullptr, w.logits, rows, s)) != PV_OK) return rc;
     }
     (void)qd;
-    return pv_k_argmax_accept(c, rows, head, s);
-}
-
-// attention alone, bf16 KV, for callers that run the projections elsewhere
-int pv_vec_attention_bf16(pv_cache *c, int layer, int rows, hipStream_t s)
-{
-    const pv_model_config &f = c->m->cfg;
-    k_attention<uint16_t><<<dim3(f.n_q_heads, rows), 256, 0, s>>>(c->ws.state, c->ws.page_table, c->ws.q, (const uint16_t *)c->d_pool,
-                                                                 c->ws.attn, pv_geom(c), layer, f.n_q_heads);
-    PV_HIP(hipGetLastError());
-    return PV_OK;
+    if (head && (rc = pv_k_argmax(c, rows, s)) != PV_OK) return rc;
+    return pv_k_finish(c, rows, nullptr, nullptr, 0, s);
 }
 
 int pv_vec_run_block(pv_cache *c, hipStream_t s)

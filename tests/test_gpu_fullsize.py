@@ -20,6 +20,7 @@ from pv_inputs import CONFIGS
 from oracle import ref
 
 pytestmark = pytest.mark.gpu
+FLIP_BOUND_L0, FLIP_BOUND = 1e-3, 0.08
 
 
 @pytest.fixture(scope="module")
@@ -79,7 +80,16 @@ def test_full_prefix_two_layers(pvlib, name, T0):
     gc, rc = _compare_steps(pvlib, gm, rm, shape, T0, (1, 4, 8, 16), 0.7, 7000)
     ge = pv_inputs.bf16_bits_to_f32(gc.export()).astype(np.float64)
     re_ = rc.export()
-    assert ge.shape == re_.shape and np.mean(ge != re_) < 0.02
+    assert ge.shape == re_.shape
+    flips = (ge != re_).mean(axis=(1, 2, 3))                 # per layer: stored bf16 K/V elements that rounded the other way
+    print(f"  K/V elements that differ from the oracle's (1 ulp of bf16), per layer: {flips}", flush=True)
+    # A stored element differs when the fp32 result falls on the other side of a bf16 rounding boundary
+    # than the fp64 one: rate = (relative error of the element) / (bf16 spacing, 2^-8 .. 2^-7).  Layer 0
+    # sees exact inputs, so its rate measures the projection arithmetic alone (16-bit operands: a few
+    # 1e-4; operands cut to 8 bits would give tens of percent).  Every flipped element below then acts
+    # as noise of 1 ulp of bf16 on a layer's inputs (rate f -> relative noise sqrt(f) * 2^-8), which is
+    # what sets the rate of the layers above: a few percent, not growing with the arithmetic error.
+    assert flips[0] < FLIP_BOUND_L0 and flips.max() < FLIP_BOUND
     assert np.abs(ge - re_).max() <= 2.0 ** -7 * np.abs(re_).max()
 
 

@@ -183,3 +183,49 @@ def test_error_paths_leave_state_untouched(pvlib, tiny_pair):
         assert gc.state() == st
     n, _ = gc.verify(12, [gc.pending])               # still usable
     assert n == 1
+
+
+@pytest.mark.parametrize("path", ["vector", "matrix"])
+def test_rows_without_a_finite_logit_are_reported(pvlib, path):
+    """A final-norm gain of NaN makes every logit NaN: no row has an arg-max.  The step must say so
+    (PV_ENUMERIC) and commit nothing, instead of returning a token id outside the vocabulary."""
+    from gpu_helpers import gpu_model
+    if path == "vector":
+        shape = CONFIGS["tiny"]
+        bad = np.full(shape.d_model, np.nan, dtype=np.float32)
+    else:
+        shape = pv_inputs.ModelShape("nan_small", 2, 128, 8, 2, 32, 192, 512, dtype="bf16", seed=99)
+        bad = np.full(shape.d_model, 0x7FC0, dtype=np.uint16)
+    m = gpu_model(shape, overrides={("final_norm", -1): bad})
+    c = pvlib.Cache(m, 64)
+    with pytest.raises(pvlib.PVError) as e:
+        c.prefill(pv_inputs.uniform_tokens(5, 12, shape.vocab))          # (one chunk on either path)
+    assert e.value.status == -6 and c.state() == (0, -1)
+    good = gpu_model(shape)
+    c2 = pvlib.Cache(good, 64)
+    c2.prefill(pv_inputs.uniform_tokens(5, 20, shape.vocab))
+    assert c2.state()[0] == 20 and 0 <= c2.pending < shape.vocab
+
+
+def test_weight_chunks_must_come_in_row_order(pvlib):
+    """Overlapping or skipped chunks may not add up to a 'complete' tensor: a chunk continues where
+    the last one ended or starts the tensor over; a model with a hole refuses to run."""
+    m = pvlib.Model(TINY)
+    w = pv_inputs.fill_tensor(TINY, "wq", 0).reshape(pv_inputs.tensor_shape(TINY, "wq"))
+    m.load_weights("wq", 0, 0, w[:64])
+    for r0 in (32, 128):                                  # overlap, gap
+        with pytest.raises(pvlib.PVError) as e:
+            m.load_weights("wq", 0, r0, w[r0:r0 + 64])
+        assert e.value.status == -2
+    m.load_weights("wq", 0, 64, w[64:])                   # in order: completes the tensor
+    m.load_weights("wq", 0, 0, w[:64])                    # starting over makes it incomplete again
+    for kind, layer in pv_inputs.iter_tensors(TINY):
+        if (kind, layer) != ("wq", 0):
+            m.load_weights(kind, layer, 0, pv_inputs.fill_tensor(TINY, kind, layer).reshape(-1, pv_inputs.tensor_shape(TINY, kind)[-1]))
+    c = pvlib.Cache(m, 32)
+    with pytest.raises(pvlib.PVError) as e:
+        c.prefill([1, 2, 3])
+    assert e.value.status == -2
+    m.load_weights("wq", 0, 64, w[64:])
+    c.prefill([1, 2, 3])
+    assert c.state()[0] == 3
