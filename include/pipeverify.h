@@ -234,6 +234,15 @@ int pv_profile_read(pv_cache *c, double *total_ms, int64_t *launches, uint64_t *
  * read under a profiler are scaled.  Asynchronous on `hip_stream`. */
 int pv_calib_copy(void *d_dst, const void *d_src, size_t nbytes, void *hip_stream);
 
+/* Plain read-only stream (k_calib_read) over `nbytes` bytes of device memory, a multiple of 16,
+ * d_src aligned to 16 bytes: every wavefront reads a contiguous slice with 16-byte loads, eight in
+ * flight per lane, and nothing is written (d_sink, 16 bytes of device memory, receives a value
+ * only if the data happens to XOR to one particular pattern).  It reads nbytes of HBM and nothing
+ * else: timed by the caller, it gives the read-stream rate this device reaches on a region of that
+ * size, the practical ceiling the weight-streaming kernels are compared with.  Asynchronous on
+ * `hip_stream`. */
+int pv_calib_read(const void *d_src, size_t nbytes, void *d_sink, void *hip_stream);
+
 const char *pv_strerror(int status);
 const char *pv_last_error(void);
 

@@ -34,7 +34,7 @@ EXPORTS = [
     "pv_cache_create", "pv_cache_destroy", "pv_cache_set_page_table", "pv_prefill", "pv_verify",
     "pv_verify_async", "pv_verify_wait", "pv_rollback", "pv_cache_len", "pv_cache_set_pending",
     "pv_debug_logits", "pv_debug_pred", "pv_cache_export", "pv_step_bytes", "pv_strerror", "pv_last_error",
-    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_cache_use_graphs", "pv_load_weights_q4",
+    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_calib_read", "pv_cache_use_graphs", "pv_load_weights_q4",
 ]
 
 _lib = None
@@ -74,6 +74,7 @@ def lib():
         L.pv_profile_select.argtypes = [vp, i32]
         L.pv_profile_read.argtypes = [vp, P(ctypes.c_double), P(i64), P(ctypes.c_uint64)]
         L.pv_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.pv_calib_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.pv_cache_use_graphs.argtypes = [vp, i32]
         L.pv_strerror.argtypes = [ctypes.c_int]; L.pv_strerror.restype = ctypes.c_char_p
         L.pv_last_error.argtypes = []; L.pv_last_error.restype = ctypes.c_char_p
@@ -103,6 +104,18 @@ def calib_copy(dst, src, stream=None):
     assert dst.numel() * dst.element_size() == n and dst.is_cuda and src.is_cuda
     _check(lib().pv_calib_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), n, _stream_ptr(stream)),
            "pv_calib_copy")
+
+
+def calib_read(src, nbytes=None, offset=0, sink=None, stream=None):
+    """Plain read-only stream over `nbytes` bytes of a device tensor, starting `offset` bytes in."""
+    total = src.numel() * src.element_size()
+    nbytes = total - offset if nbytes is None else nbytes
+    assert src.is_cuda and offset % 16 == 0 and nbytes % 16 == 0 and offset + nbytes <= total
+    if sink is None:
+        sink = torch.zeros(16, dtype=torch.uint8, device=src.device)
+    _check(lib().pv_calib_read(ctypes.c_void_p(src.data_ptr() + offset), nbytes, ctypes.c_void_p(sink.data_ptr()),
+                               _stream_ptr(stream)), "pv_calib_read")
+    return sink
 
 
 class Model:
