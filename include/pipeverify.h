@@ -172,6 +172,23 @@ int pv_verify_async(pv_cache *c, int32_t prefix_len, const int32_t *draft, int32
 int pv_verify_wait(pv_cache *c, int32_t *accepted_len, int32_t *next_token);
 
 /*
+ * pv_verify_async for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same step, same results through pv_verify_wait, but it
+ * calls no allocating routine (no graph is instantiated, no stream or event is created) and the
+ * per-step buffers (activations, operands, partial sums, logits) are taken from one fixed device
+ * array inside the library of PV_STATIC_SCRATCH_BYTES bytes, which each GPU the library runs on
+ * holds until the process ends, instead of from the cache's workspace; cache state, page table and
+ * K/V pages stay in the caller's buffers.  A step that needs more (large vocabulary x gamma, very
+ * long max_tokens) is refused with PV_ENOMEM and nothing is changed.  The array is cleared by a
+ * kernel at the start of every call.  Every cache of every model on a GPU shares that GPU's array:
+ * two such calls that overlap in time on one GPU (different streams or threads) race; calls on
+ * one stream, or separated by pv_verify_wait, do not.  The block's logits are not kept for
+ * pv_debug_logits.  Instrumentation (pv_profile_select) must be off.
+ */
+#define PV_STATIC_SCRATCH_BYTES (32u << 20)
+int pv_verify_async_static(pv_cache *c, int32_t prefix_len, const int32_t *draft, int32_t gamma, void *hip_stream);
+
+/*
  * Truncate the cache to its first new_len tokens (0 <= new_len <= length, else PV_ERANGE)
  * and forget pending, so the next block's first token is trusted: it is the correction
  * token of the stage that asked for the rollback.  Metadata only.  Synchronises hip_stream.

@@ -34,7 +34,7 @@ EXPORTS = [
     "pv_cache_create", "pv_cache_destroy", "pv_cache_set_page_table", "pv_prefill", "pv_verify",
     "pv_verify_async", "pv_verify_wait", "pv_rollback", "pv_cache_len", "pv_cache_set_pending",
     "pv_debug_logits", "pv_debug_pred", "pv_cache_export", "pv_step_bytes", "pv_strerror", "pv_last_error",
-    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_calib_read", "pv_cache_use_graphs", "pv_load_weights_q4",
+    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_calib_read", "pv_verify_async_static", "pv_cache_use_graphs", "pv_load_weights_q4",
 ]
 
 _lib = None
@@ -62,6 +62,7 @@ def lib():
         L.pv_prefill.argtypes = [vp, vp, i32, vp]
         L.pv_verify.argtypes = [vp, i32, vp, i32, P(i32), P(i32), vp]
         L.pv_verify_async.argtypes = [vp, i32, vp, i32, vp]
+        L.pv_verify_async_static.argtypes = [vp, i32, vp, i32, vp]
         L.pv_verify_wait.argtypes = [vp, P(i32), P(i32)]
         L.pv_rollback.argtypes = [vp, i32, vp]
         L.pv_cache_readmit.argtypes = [vp, i32, i32, vp]
@@ -213,6 +214,12 @@ class Cache:
         a = np.ascontiguousarray(draft, dtype=np.int32)
         with self._dev():
             _check(self.L.pv_verify_async(self.h, prefix_len, a.ctypes.data, len(a), _stream_ptr(stream)), "pv_verify_async")
+
+    def verify_async_static(self, prefix_len, draft, stream=None):
+        """The step without any allocation: per-step buffers in the library's fixed device array."""
+        a = np.ascontiguousarray(draft, dtype=np.int32)
+        with self._dev():
+            _check(self.L.pv_verify_async_static(self.h, prefix_len, a.ctypes.data, len(a), _stream_ptr(stream)), "pv_verify_async_static")
 
     def verify_wait(self):
         n, t = ctypes.c_int32(), ctypes.c_int32()

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 #include <string.h>
 #include <new>
+#include <mutex>
 #include "pv_kernels_common.h"
 
 static thread_local char g_err[512] = "";
@@ -584,6 +585,77 @@ extern "C" int pv_verify_async(pv_cache *c, int32_t prefix_len, const int32_t *d
     if (rc != PV_OK) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     rc = enqueue_block(c, draft, gamma, PV_MODE_VERIFY, s);
+    if (rc != PV_OK) return rc;
+    c->in_flight = true; c->flight_stream = s;
+    return PV_OK;
+}
+
+// ---- the step for callers that may not allocate ----
+//
+// One fixed device array stands in for the per-step part of the cache's workspace (activations,
+// operands, partial sums, logits, arg-max candidates).  In host code the array's name is only a
+// stand-in for the symbol: its device address is looked up once per device and kept.
+#define PV_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[PV_STATIC_SCRATCH_BYTES];
+static char *g_scratch_ptr[PV_MAX_DEVICES];
+static std::mutex g_scratch_mu;
+
+static int static_scratch(char **out)
+{
+    int dev = -1;
+    PV_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= PV_MAX_DEVICES) { pv_set_error("device index %d outside [0, %d)", dev, PV_MAX_DEVICES); return PV_EINVAL; }
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        PV_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));      // this device's copy of the array
+        if (!p) { pv_set_error("hipGetSymbolAddress returned a null address"); return PV_EHIP; }
+        g_scratch_ptr[dev] = (char *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return PV_OK;
+}
+
+__global__ void __launch_bounds__(256) k_zero(uint4 *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+extern "C" int pv_verify_async_static(pv_cache *c, int32_t prefix_len, const int32_t *draft, int32_t gamma, void *hip_stream)
+{
+    int rc = verify_checks(c, prefix_len, draft, gamma);
+    if (rc != PV_OK) return rc;
+    if (c->prof_kind != PV_PROF_NONE) { pv_set_error("kernel instrumentation is switched on for this cache"); return PV_ESTATE; }
+    const pv_model *m = c->m;
+    // per-step buffers for a block of this size, laid out in the fixed array (the same layout routine
+    // as a workspace; the cache state and the page table stay where the cache keeps them)
+    const int cap = (gamma + PV_ROW_PAD - 1) / PV_ROW_PAD * PV_ROW_PAD;
+    const size_t need = layout_ws(m, cap, c->n_pages, nullptr, nullptr);
+    if (need > PV_STATIC_SCRATCH_BYTES) {
+        pv_set_error("a %d-row step of this model with max_tokens %d needs %zu bytes of per-step buffers, the fixed array holds %zu",
+                     gamma, c->max_tokens, need, (size_t)PV_STATIC_SCRATCH_BYTES);
+        return PV_ENOMEM;
+    }
+    char *base = nullptr;
+    if ((rc = static_scratch(&base)) != PV_OK) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    // the array keeps the last call's contents (of any cache, any model): start from zeros, as a fresh workspace does
+    k_zero<<<1024, 256, 0, s>>>((uint4 *)base, need / 16);
+    PV_HIP(hipGetLastError());
+    const pv_ws own = c->ws;
+    const int own_cap = c->rows_cap;
+    layout_ws(m, cap, c->n_pages, &c->ws, base);
+    c->ws.state = own.state; c->ws.page_table = own.page_table;
+    c->rows_cap = cap;
+    for (int j = 0; j < gamma; ++j)
+        if (draft[j] < 0 || draft[j] >= m->cfg.vocab) { c->ws = own; c->rows_cap = own_cap; pv_set_error("token id %d at position %d outside [0, %d)", draft[j], j, m->cfg.vocab); return PV_ERANGE; }
+    memcpy(c->io->draft, draft, sizeof(int32_t) * gamma);
+    c->io->hdr[2] = gamma; c->io->hdr[3] = PV_MODE_VERIFY;
+    c->last_rows = gamma;
+    c->blk_start = c->len; c->blk_rows = gamma;
+    rc = record_block(c, gamma, PV_MODE_VERIFY, s);      // plain launches: the kernels take the buffers as arguments
+    c->ws = own; c->rows_cap = own_cap;
+    c->last_rows = 0;                                   // the block's logits are in the shared array: not kept for pv_debug_logits
     if (rc != PV_OK) return rc;
     c->in_flight = true; c->flight_stream = s;
     return PV_OK;
