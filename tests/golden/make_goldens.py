@@ -166,7 +166,11 @@ def make_chain(shape, T, alphas, gammas, out):
             n_r, t_r, pred_r, lg = c.verify(Tk, d, want_logits=True)
             n, nxt, pred = rec.add(Tk, pending, alpha, d, lg)
             assert (n, nxt) == (n_r, t_r) and np.array_equal(pred, pred_r)          # the recorder's rule is ref_verify's
-            assert np.array_equal(d[:n], blk[:n]) and (n == 0 or nxt == G[have + n] if have + n < len(G) else True)   # lossless
+            assert np.array_equal(d[:n], blk[:n])                                      # only greedy tokens are ever accepted
+            if have + n == len(G):                    # the whole known continuation was accepted: the correction token extends it
+                mrow = np.sort(lg[n - 1])
+                G.append(nxt); Gm.append(float(mrow[-1] - mrow[-2]))
+            assert nxt == G[have + n]
             log(f"{shape.name}: alpha {alpha} step {k}: T {Tk} gamma {g} accepted {n} next {nxt}")
             Tk, pending, trust = Tk + n, nxt, n == 0
         chains.append((step0, len(rec.rows["T"]), np.array(G, dtype=np.int32), np.array(Gm)))

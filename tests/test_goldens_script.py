@@ -8,7 +8,7 @@ import numpy as np
 
 import pv_inputs
 from oracle import ref, replay
-from helpers import ref_model
+from helpers import ref_model, greedy_continuation
 
 GQA = pv_inputs.ModelShape("gqa_small", 3, 128, 8, 2, 32, 176, 512, rope_base=500000.0, dtype="bf16", seed=4242)
 
@@ -53,6 +53,11 @@ def test_golden_script_records_what_the_plain_oracle_computes(tmp_path):
         c = ref.RefCache(rm, 160, ref.KV_BF16)
         c.prefill(prompt)
         assert c.pending == g["chain0_greedy"][0]
+        for ci in range(2):                                  # the recorded greedy continuations are the plain single-token ones
+            if f"chain{ci}_greedy" in g.files:
+                G = g[f"chain{ci}_greedy"]
+                assert np.array_equal(G, greedy_continuation(c, len(G)))
+                c.rollback(100); c.pending = int(G[0])
         ex = c.export()
         assert np.array_equal(ex[g["kv_layers"]][:, :, g["kv_pos"], :].astype(np.float32), g["kv_sample"])
         seen_accepts = set()
