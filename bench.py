@@ -16,7 +16,8 @@ step's stream in a second, instrumented pass over the same steps; `stream_ceilin
 read-only stream of the step's byte count reaches on this device in this run; `cpu_baseline` =
 the CPU oracle timed on a bounded slice of the same workload.  With no --workload / --gamma
 given, `also` carries the other points of the metric measured the same way in the same run:
-the 8B shape at gamma 1, 4, 16 and the 70B-shaped verifier (prefix 1024, gamma 8).
+the 8B shape at gamma 1, 4, 16, batched verification of 4 sequences x gamma 8 on the 8B shape, and the
+70B-shaped verifier (prefix 1024, gamma 8).
 """
 import argparse
 import gc
@@ -198,6 +199,62 @@ class Workload:
                              "bytes_per_launch": kbytes, "avg_launch_us": k_ms * 1e3, "launches": launches}
         return r
 
+    def run_batch(self, n_seq, gamma, alpha, K, W):
+        """Batched verification: n_seq sequences (this one + n_seq - 1 more caches with prompts of their own),
+        gamma drafts each, one pass over the weights per step.  Same timing discipline as run()."""
+        import numpy as np
+        import torch
+        pv, pvi, shape, T0 = self.pv, self.pvi, self.shape, self.T0
+        n_steps = K + W
+        caches, Gs = [self.cache], [self.G]
+        need = n_steps * gamma + gamma + 1
+        t0 = time.time()
+        for i in range(1, n_seq):
+            c = pv.Cache(self.model, self.cache.max_tokens)
+            c.prefill(pvi.uniform_tokens(2000 + shape.seed + 17 * i, T0, shape.vocab))
+            G = np.empty(need, dtype=np.int32)
+            G[0] = c.pending
+            for k in range(1, need):
+                n, nxt = c.verify(T0 + k - 1, G[k - 1:k])
+                G[k] = nxt
+            caches.append(c); Gs.append(G)
+        log(f"{self.name}: {n_seq - 1} more sequences prefilled and pre-passed: {time.time() - t0:.2f}s")
+        for c, G in zip(caches, Gs):
+            c.rollback(T0); c.set_pending(int(G[0]))
+        trust = [False] * n_seq
+
+        def steps(first, count):
+            acc = 0
+            for st in range(first, first + count):
+                drafts = []
+                for i, (c, G) in enumerate(zip(caches, Gs)):
+                    T = len(c)
+                    blk = G[T - T0: T - T0 + gamma]
+                    d = pvi.perturb_drafts(blk, alpha, shape.vocab, 3000 + shape.seed + 1000 * i, st)
+                    if trust[i]:
+                        d[0] = blk[0]
+                    drafts.append(d)
+                res = pv.verify_batch(caches, drafts)
+                for i, (n, _) in enumerate(res):
+                    acc += n; trust[i] = n == 0
+            return acc
+        steps(0, W)
+        kv_tok = shape.kv_bytes_per_token()
+        weights = self.cache.step_bytes(gamma) - kv_tok * (len(self.cache) + 2 * gamma)
+        bytes_first = weights + sum(kv_tok * (len(c) + 2 * gamma) for c in caches)
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        accepted = steps(W, K)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_start
+        step_bytes = 0.5 * (bytes_first + weights + sum(kv_tok * (len(c) + 2 * gamma) for c in caches))
+        for c in caches[1:]:
+            c.close()
+        return {"sequences": n_seq, "gamma": gamma, "rows": n_seq * gamma, "prefix": T0, "alpha": alpha, "ms_per_step": elapsed / K * 1e3,
+                "steps_per_s": K / elapsed, "verified_tokens_per_s": n_seq * gamma * K / elapsed, "committed_tokens_per_s": accepted / elapsed,
+                "mean_accepted_len": accepted / K / n_seq, "step_bytes": step_bytes,
+                "step_hbm_gbps": step_bytes / (elapsed / K) / 1e9, "step_hbm_frac": step_bytes / (elapsed / K) / 1e9 / HBM_PEAK_GBPS}
+
     def stream_ceiling(self, step_bytes, launch_bytes):
         """Plain read-only streams over the weight arena, timed with events on the stream they run on:
         one of the step's byte count, and launches of one kernel's byte count over successive regions
@@ -252,6 +309,8 @@ def main():
     ap.add_argument("--alpha", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true", help="headline workload only (no gamma sweep, no 70B-shaped run)")
+    ap.add_argument("--batch", type=int, default=None, metavar="B",
+                    help="also time batched verification of B sequences x gamma drafts (default run: 4)")
     ap.add_argument("--no-graphs", action="store_true", help="plain launches instead of HIP-graph replay of the step (comparison runs)")
     ap.add_argument("--prof-kernel", default="gateup")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
@@ -288,6 +347,12 @@ def main():
             if g != gamma:
                 also[f"{name}_gamma{g}"] = with_ceiling(wl.run(g, alpha, K, W), ceil)
                 log(f"{name} gamma {g}: {also[f'{name}_gamma{g}']['ms_per_step']:.3f} ms/step")
+
+    n_batch = a.batch if a.batch is not None else (4 if sweep else 0)
+    if n_batch > 1:
+        rb = with_ceiling(wl.run_batch(n_batch, gamma, alpha, K, W), ceil)
+        also[f"{name}_batch{n_batch}_gamma{gamma}"] = rb
+        log(f"{name} batch {n_batch} x gamma {gamma}: {rb['ms_per_step']:.3f} ms/step")
 
     if a.calib_copy > 0:
         src = torch.full((a.calib_copy << 20,), 1, dtype=torch.uint8, device="cuda")

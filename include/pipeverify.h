@@ -172,6 +172,22 @@ int pv_verify_async(pv_cache *c, int32_t prefix_len, const int32_t *draft, int32
 int pv_verify_wait(pv_cache *c, int32_t *accepted_len, int32_t *next_token);
 
 /*
+ * Verify the blocks of several sequences in one pass over the weights (Sec. 2.2: verification pays
+ * because the weight and KV-cache loads are shared by all the tokens of a step; stacking the blocks
+ * of independent sequences shares the weight loads further).  caches[0..n_seq): distinct caches of
+ * one bf16 model on the matrix path, all created with the same max_tokens; sequence i contributes
+ * gamma[i] draft tokens, draft = their concatenation (host arrays), sum of gamma[i] <= 64 (<= 16 with
+ * 4-bit weights), n_seq <= 16.  Every sequence is verified exactly as pv_verify would verify it alone
+ * (same rule, its own prefix_len guard, pending token, K/V pages and in-step rollback); on return
+ * accepted_len[i] / next_token[i] hold its results.  The stacked activations use the workspace of
+ * caches[0], whose pv_debug_logits then returns all rows in order.  Nothing is changed if a check fails.
+ * PV_ENOMEM: the batch needs more attention row groups than the workspace holds (each sequence rounds
+ * its gamma x (q heads per kv head) query rows up to a multiple of 32).  Synchronises hip_stream.
+ */
+int pv_verify_batch(pv_cache *const *caches, int32_t n_seq, const int32_t *prefix_len, const int32_t *draft,
+                    const int32_t *gamma, int32_t *accepted_len, int32_t *next_token, void *hip_stream);
+
+/*
  * pv_verify_async for callers that cannot allocate: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  Same step, same results through pv_verify_wait, but it
  * calls no allocating routine (no graph is instantiated, no stream or event is created) and the

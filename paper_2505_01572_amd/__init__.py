@@ -5,5 +5,5 @@ the path runs in the library's HIP kernels; Python only marshals arguments and u
 for device memory and streams.
 """
 from .binding import (  # noqa: F401
-    PVError, lib, Model, Cache, KINDS, PV_F32, PV_BF16, PATH_AUTO, PATH_VECTOR, PATH_MATRIX, PROF, calib_copy, calib_read,
+    PVError, lib, Model, Cache, KINDS, PV_F32, PV_BF16, PATH_AUTO, PATH_VECTOR, PATH_MATRIX, PROF, calib_copy, calib_read, verify_batch,
 )

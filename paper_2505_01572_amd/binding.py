@@ -34,7 +34,7 @@ EXPORTS = [
     "pv_cache_create", "pv_cache_destroy", "pv_cache_set_page_table", "pv_prefill", "pv_verify",
     "pv_verify_async", "pv_verify_wait", "pv_rollback", "pv_cache_len", "pv_cache_set_pending",
     "pv_debug_logits", "pv_debug_pred", "pv_cache_export", "pv_step_bytes", "pv_strerror", "pv_last_error",
-    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_calib_read", "pv_verify_async_static", "pv_cache_use_graphs", "pv_load_weights_q4",
+    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_calib_read", "pv_verify_async_static", "pv_verify_batch", "pv_cache_use_graphs", "pv_load_weights_q4",
 ]
 
 _lib = None
@@ -64,6 +64,7 @@ def lib():
         L.pv_verify_async.argtypes = [vp, i32, vp, i32, vp]
         L.pv_verify_async_static.argtypes = [vp, i32, vp, i32, vp]
         L.pv_verify_wait.argtypes = [vp, P(i32), P(i32)]
+        L.pv_verify_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
         L.pv_rollback.argtypes = [vp, i32, vp]
         L.pv_cache_readmit.argtypes = [vp, i32, i32, vp]
         L.pv_cache_len.argtypes = [vp, P(i32), P(i32)]
@@ -117,6 +118,22 @@ def calib_read(src, nbytes=None, offset=0, sink=None, stream=None):
     _check(lib().pv_calib_read(ctypes.c_void_p(src.data_ptr() + offset), nbytes, ctypes.c_void_p(sink.data_ptr()),
                                _stream_ptr(stream)), "pv_calib_read")
     return sink
+
+
+def verify_batch(caches, drafts, stream=None):
+    """Blocks of several sequences in one pass over the weights.  caches: Cache objects of one model,
+    drafts: one token list per cache.  Returns [(accepted_len, next_token), ...]."""
+    n = len(caches)
+    assert n == len(drafts) and n >= 1
+    ptrs = (ctypes.c_void_p * n)(*[c.h for c in caches])
+    gam = np.array([len(d) for d in drafts], dtype=np.int32)
+    flat = np.ascontiguousarray(np.concatenate([np.asarray(d, dtype=np.int32) for d in drafts]), dtype=np.int32)
+    pre = np.array([len(c) for c in caches], dtype=np.int32)
+    acc, nxt = np.empty(n, dtype=np.int32), np.empty(n, dtype=np.int32)
+    with caches[0]._dev():
+        _check(lib().pv_verify_batch(ptrs, n, pre.ctypes.data, flat.ctypes.data, gam.ctypes.data, acc.ctypes.data, nxt.ctypes.data,
+                                     _stream_ptr(stream)), "pv_verify_batch")
+    return [(int(a), int(t)) for a, t in zip(acc, nxt)]
 
 
 class Model:

@@ -254,7 +254,7 @@ static int model_complete(const pv_model *m)
 }
 
 // ---- workspace layout ----
-static size_t layout_ws(const pv_model *m, int rows_cap, int n_pages, pv_ws *w, char *base)
+static size_t layout_ws(const pv_model *m, int rows_cap, int units_cap, int n_pages, pv_ws *w, char *base)
 {
     const pv_model_config &c = m->cfg;
     size_t off = 0;
@@ -273,7 +273,7 @@ static size_t layout_ws(const pv_model *m, int rows_cap, int n_pages, pv_ws *w, 
     p = take(4 * R * c.ffn_dim); if (w) w->gate = (float *)p;
     p = take(4 * R * c.ffn_dim); if (w) w->up = (float *)p;
     p = take(4 * R * (size_t)c.vocab); if (w) w->logits = (float *)p;
-    const size_t pf = m->path >= PV_PATH_MATRIX ? pv_mat_part_floats(m, rows_cap, n_pages * m->cfg.page_tokens) : 0;
+    const size_t pf = m->path >= PV_PATH_MATRIX ? pv_mat_part_floats(m, rows_cap, units_cap, n_pages * m->cfg.page_tokens) : 0;
     p = take(4 * pf + 256); if (w) { w->part = (float *)p; w->part_floats = pf; }
     return off;
 }
@@ -286,6 +286,8 @@ static inline int prefill_rows_of(const pv_model *m)
     return (m->path >= PV_PATH_MATRIX && m->wbits != 4 && m->cfg.max_gamma < PV_MAX_ROWS) ? PV_MAX_ROWS : m->cfg.max_gamma;
 }
 static inline int rows_cap_of(const pv_model *m) { return (prefill_rows_of(m) + PV_ROW_PAD - 1) / PV_ROW_PAD * PV_ROW_PAD; }
+// a workspace's attention partials: one sequence of rows_cap rows, or a batch (every further sequence rounds its rows up to whole units)
+static inline int units_cap_of(const pv_model *m) { return m->path >= PV_PATH_MATRIX ? pv_attn_units(m, rows_cap_of(m)) + PV_MAX_SEQ - 1 : 0; }
 
 extern "C" int pv_cache_bytes(const pv_model *m, int32_t max_tokens, size_t *page_pool_bytes, size_t *workspace_bytes)
 {
@@ -294,7 +296,7 @@ extern "C" int pv_cache_bytes(const pv_model *m, int32_t max_tokens, size_t *pag
     const pv_model_config &c = m->cfg;
     const int n_pages = (max_tokens + c.page_tokens - 1) / c.page_tokens;
     *page_pool_bytes = align_up((size_t)c.n_layers * n_pages * c.n_kv_heads * 2 * c.page_tokens * c.head_dim * m->elt, 256);
-    *workspace_bytes = layout_ws(m, rows_cap_of(m), n_pages, nullptr, nullptr);
+    *workspace_bytes = layout_ws(m, rows_cap_of(m), units_cap_of(m), n_pages, nullptr, nullptr);
     return PV_OK;
 }
 
@@ -313,9 +315,9 @@ extern "C" int pv_cache_create(const pv_model *m, void *d_page_pool, size_t page
     c->m = m; c->d_pool = (char *)d_page_pool; c->pool_bytes = page_pool_bytes;
     c->d_ws = (char *)d_workspace; c->ws_bytes = workspace_bytes;
     c->max_tokens = max_tokens; c->n_pages = (max_tokens + m->cfg.page_tokens - 1) / m->cfg.page_tokens;
-    c->rows_cap = rows_cap_of(m);
-    layout_ws(m, c->rows_cap, c->n_pages, &c->ws, c->d_ws);
-    c->len = 0; c->pending = -1; c->last_rows = 0; c->blk_start = 0; c->blk_rows = 0; c->in_flight = false; c->flight_stream = nullptr; c->io = nullptr;
+    c->rows_cap = rows_cap_of(m); c->units_cap = units_cap_of(m);
+    layout_ws(m, c->rows_cap, c->units_cap, c->n_pages, &c->ws, c->d_ws);
+    c->len = 0; c->pending = -1; c->last_rows = 0; c->blk_start = 0; c->blk_rows = 0; c->blk_units = 0; c->blk_seq_rows = 0; c->in_flight = false; c->flight_stream = nullptr; c->io = nullptr;
     c->prof_kind = PV_PROF_NONE; c->prof_pending = 0; c->prof_ev = nullptr; c->prof_ms = 0; c->prof_launches = 0;
     c->use_graphs = true; c->cap_stream = nullptr;
     for (auto &row : c->gexec) for (auto &ge : row) ge = nullptr;
@@ -335,6 +337,11 @@ extern "C" int pv_cache_create(const pv_model *m, void *d_page_pool, size_t page
     if (e == hipSuccess) e = hipMemcpy(c->ws.page_table, ident, sizeof(int32_t) * c->n_pages, hipMemcpyHostToDevice);
     free(ident);
     pv_dev_state st; memset(&st, 0, sizeof(st)); st.pending = -1;
+    // a plain step's block is one sequence: this cache
+    c->io->single.n_seq = 1;
+    c->io->single.seq[0].st = c->ws.state; c->io->single.seq[0].pool = c->d_pool; c->io->single.seq[0].page_table = c->ws.page_table;
+    c->io->single.seq[0].gamma = 0; c->io->single.seq[0].row0 = 0; c->io->single.seq[0].n_pages = c->n_pages; c->io->single.seq[0].unit0 = 0;
+    st.blk = c->io->single;
     if (e == hipSuccess) e = hipMemcpy(c->ws.state, &st, sizeof(st), hipMemcpyHostToDevice);
     if (e != hipSuccess) { pv_set_error("cache initialisation failed: %s", hipGetErrorString(e)); (void)hipHostFree(c->io); delete c; return PV_EHIP; }
     *out = c;
@@ -535,7 +542,7 @@ static int absorb_result(pv_cache *c)
     prof_collect(c);
     c->len += c->io->result[0];
     c->pending = c->io->result[1];
-    if (c->io->result[2]) { pv_set_error("a row of the block has no finite logit (non-finite weights or activations); nothing was committed"); return PV_ENUMERIC; }
+    if (c->io->result[PV_RESULT_ERR]) { pv_set_error("a row of the block has no finite logit (non-finite weights or activations); nothing was committed"); return PV_ENUMERIC; }
     return PV_OK;
 }
 
@@ -630,7 +637,8 @@ extern "C" int pv_verify_async_static(pv_cache *c, int32_t prefix_len, const int
     // per-step buffers for a block of this size, laid out in the fixed array (the same layout routine
     // as a workspace; the cache state and the page table stay where the cache keeps them)
     const int cap = (gamma + PV_ROW_PAD - 1) / PV_ROW_PAD * PV_ROW_PAD;
-    const size_t need = layout_ws(m, cap, c->n_pages, nullptr, nullptr);
+    const int ucap = m->path >= PV_PATH_MATRIX ? pv_attn_units(m, cap) : 0;          // one sequence: no batch allowance
+    const size_t need = layout_ws(m, cap, ucap, c->n_pages, nullptr, nullptr);
     if (need > PV_STATIC_SCRATCH_BYTES) {
         pv_set_error("a %d-row step of this model with max_tokens %d needs %zu bytes of per-step buffers, the fixed array holds %zu",
                      gamma, c->max_tokens, need, (size_t)PV_STATIC_SCRATCH_BYTES);
@@ -643,18 +651,18 @@ extern "C" int pv_verify_async_static(pv_cache *c, int32_t prefix_len, const int
     k_zero<<<1024, 256, 0, s>>>((uint4 *)base, need / 16);
     PV_HIP(hipGetLastError());
     const pv_ws own = c->ws;
-    const int own_cap = c->rows_cap;
-    layout_ws(m, cap, c->n_pages, &c->ws, base);
+    const int own_cap = c->rows_cap, own_ucap = c->units_cap;
+    layout_ws(m, cap, ucap, c->n_pages, &c->ws, base);
     c->ws.state = own.state; c->ws.page_table = own.page_table;
-    c->rows_cap = cap;
+    c->rows_cap = cap; c->units_cap = ucap;
     for (int j = 0; j < gamma; ++j)
-        if (draft[j] < 0 || draft[j] >= m->cfg.vocab) { c->ws = own; c->rows_cap = own_cap; pv_set_error("token id %d at position %d outside [0, %d)", draft[j], j, m->cfg.vocab); return PV_ERANGE; }
+        if (draft[j] < 0 || draft[j] >= m->cfg.vocab) { c->ws = own; c->rows_cap = own_cap; c->units_cap = own_ucap; pv_set_error("token id %d at position %d outside [0, %d)", draft[j], j, m->cfg.vocab); return PV_ERANGE; }
     memcpy(c->io->draft, draft, sizeof(int32_t) * gamma);
     c->io->hdr[2] = gamma; c->io->hdr[3] = PV_MODE_VERIFY;
     c->last_rows = gamma;
     c->blk_start = c->len; c->blk_rows = gamma;
     rc = record_block(c, gamma, PV_MODE_VERIFY, s);      // plain launches: the kernels take the buffers as arguments
-    c->ws = own; c->rows_cap = own_cap;
+    c->ws = own; c->rows_cap = own_cap; c->units_cap = own_ucap;
     c->last_rows = 0;                                   // the block's logits are in the shared array: not kept for pv_debug_logits
     if (rc != PV_OK) return rc;
     c->in_flight = true; c->flight_stream = s;
@@ -680,6 +688,68 @@ extern "C" int pv_verify(pv_cache *c, int32_t prefix_len, const int32_t *draft, 
     int rc = pv_verify_async(c, prefix_len, draft, gamma, hip_stream);
     if (rc != PV_OK) return rc;
     return pv_verify_wait(c, accepted_len, next_token);
+}
+
+// ---- several sequences in one pass over the weights ----
+extern "C" int pv_verify_batch(pv_cache *const *caches, int32_t n_seq, const int32_t *prefix_len, const int32_t *draft,
+                               const int32_t *gamma, int32_t *accepted_len, int32_t *next_token, void *hip_stream)
+{
+    if (!caches || !prefix_len || !draft || !gamma || !accepted_len || !next_token) { pv_set_error("null pointer"); return PV_EINVAL; }
+    if (n_seq < 1 || n_seq > PV_MAX_SEQ) { pv_set_error("n_seq %d outside [1, %d]", n_seq, PV_MAX_SEQ); return PV_ERANGE; }
+    pv_cache *lead = caches[0];
+    int rc = check_ready(lead);
+    if (rc != PV_OK) return rc;
+    const pv_model *m = lead->m;
+    if (m->path < PV_PATH_MATRIX) { pv_set_error("batched verification runs on the matrix path (bf16 models)"); return PV_EINVAL; }
+    if (lead->prof_kind != PV_PROF_NONE) { pv_set_error("kernel instrumentation is switched on for the first cache"); return PV_ESTATE; }
+    int rows = 0, units = 0, seq_rows = 0;
+    for (int i = 0; i < n_seq; ++i) {
+        pv_cache *c = caches[i];
+        if (!c) { pv_set_error("null cache %d", i); return PV_EINVAL; }
+        for (int k = 0; k < i; ++k) if (caches[k] == c) { pv_set_error("cache %d appears twice in the batch", i); return PV_EINVAL; }
+        if (c->m != m) { pv_set_error("cache %d belongs to another model", i); return PV_EINVAL; }
+        if (c->max_tokens != lead->max_tokens) { pv_set_error("caches of a batch must have the same max_tokens (%d vs %d)", c->max_tokens, lead->max_tokens); return PV_EINVAL; }
+        if ((rc = verify_checks(c, prefix_len[i], draft + rows, gamma[i])) != PV_OK) return rc;
+        rows += gamma[i];
+    }
+    if (rows > lead->rows_cap || (m->wbits == 4 && rows > 16)) { pv_set_error("%d rows in all: a step of this model takes at most %d", rows, m->wbits == 4 ? 16 : lead->rows_cap); return PV_ERANGE; }
+    for (int j = 0; j < rows; ++j)
+        if (draft[j] < 0 || draft[j] >= m->cfg.vocab) { pv_set_error("token id %d at row %d outside [0, %d)", draft[j], j, m->cfg.vocab); return PV_ERANGE; }
+    // the block's description: rows and attention row-group units of every sequence, in order
+    pv_block_desc &bd = lead->io->batch;
+    bd.n_seq = n_seq;
+    int r0 = 0;
+    for (int i = 0; i < n_seq; ++i) {
+        pv_cache *c = caches[i];
+        pv_seq_ref &sq = bd.seq[i];
+        sq.st = c->ws.state; sq.pool = c->d_pool; sq.page_table = c->ws.page_table;
+        sq.gamma = gamma[i]; sq.row0 = r0; sq.n_pages = c->n_pages; sq.unit0 = units;
+        r0 += gamma[i];
+        units += pv_attn_units(m, gamma[i]);
+        if (gamma[i] > seq_rows) seq_rows = gamma[i];
+    }
+    if (units > lead->units_cap) { pv_set_error("the batch needs %d attention row groups, the workspace holds %d", units, lead->units_cap); return PV_ENOMEM; }
+    memcpy(lead->io->draft, draft, sizeof(int32_t) * rows);
+    lead->io->hdr[2] = rows; lead->io->hdr[3] = PV_MODE_VERIFY;
+    hipStream_t s = (hipStream_t)hip_stream;
+    // description in, the step as plain launches, the cache's own one-sequence description back in
+    PV_HIP(hipMemcpyAsync(&lead->ws.state->blk, &bd, sizeof(pv_block_desc), hipMemcpyHostToDevice, s));
+    lead->last_rows = rows; lead->blk_units = units; lead->blk_seq_rows = seq_rows;
+    rc = record_block(lead, rows, PV_MODE_VERIFY, s);
+    lead->blk_units = 0; lead->blk_seq_rows = 0;
+    const hipError_t e1 = hipMemcpyAsync(&lead->ws.state->blk, &lead->io->single, sizeof(pv_block_desc), hipMemcpyHostToDevice, s);
+    const hipError_t e2 = hipStreamSynchronize(s);
+    if (rc != PV_OK) return rc;
+    if (e1 != hipSuccess || e2 != hipSuccess) { pv_set_error("batched step failed: %s", hipGetErrorString(e1 != hipSuccess ? e1 : e2)); return PV_EHIP; }
+    for (int i = 0; i < n_seq; ++i) {
+        pv_cache *c = caches[i];
+        accepted_len[i] = lead->io->result[2 * i]; next_token[i] = lead->io->result[2 * i + 1];
+        c->blk_start = c->len; c->blk_rows = gamma[i];
+        c->len += accepted_len[i]; c->pending = next_token[i];
+        if (c != lead) c->last_rows = 0;
+    }
+    if (lead->io->result[PV_RESULT_ERR]) { pv_set_error("a row of the block has no finite logit (non-finite weights or activations)"); return PV_ENUMERIC; }
+    return PV_OK;
 }
 
 extern "C" int pv_rollback(pv_cache *c, int32_t new_len, void *hip_stream)

@@ -62,22 +62,34 @@ __host__ __device__ constexpr int attn_smem_floats() { return 8 * 16 * (HD + 4) 
 // 512 threads must call).  TILES as above; chunk c covers keys c * (256 / TILES) ... .
 // smem: attn_smem_floats<HD>() floats of LDS (more than 64 KiB for HD = 128: dynamic).
 template <int HD, int TILES>
-__device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int mp, int n_mp, float *smem)
+__device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int z, int n_units, float *smem)
 {
     constexpr int KS = HD / 32, ET = HD / 16, OS = HD + 4, NWM = 8 / TILES, CK = 256 / TILES;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, jl = lane & 15, g = lane >> 4;
     const int rt = wave / NWM, kq = wave % NWM;
-    const pv_kv_geom &gm = a.geom;
+    pv_kv_geom gm = a.geom;
     const int sub_shift = gm.page_shift - 4, sub_mask = (1 << sub_shift) - 1;
     // this wave's 32 keys: two groups of 16.  Which pages they sit in does not depend on the cache
     // length, so the page-table entries are fetched beside the length, not behind it (an entry past
     // the table's end is clamped; such keys are past the length as well and never used).
     const int p0 = c * CK + kq * 32;
-    const int pg0 = min((p0 >> 4) >> sub_shift, a.n_pages - 1), pg1 = min(((p0 >> 4) + 1) >> sub_shift, a.n_pages - 1);
-    const int ph0 = a.page_table[pg0], ph1g = a.page_table[pg1];
-    const int len = a.st->len, gamma = a.st->gamma, nkeys = len + gamma;
+    int ph0 = a.page_table[min((p0 >> 4) >> sub_shift, a.n_pages - 1)], ph1g = a.page_table[min(((p0 >> 4) + 1) >> sub_shift, a.n_pages - 1)];
+    const int nseq = a.st->blk.n_seq;
+    int len = a.st->len, gamma = a.st->gamma, row0 = 0, mp = z;
+    const uint16_t *pool = a.pool;
+    if (nseq > 1) {
+        // batched step: unit z belongs to the sequence with the largest unit0 <= z; its rows, length and pages
+        int sidx = 0;
+        for (int k = 1; k < nseq; ++k) if (z >= a.st->blk.seq[k].unit0) sidx = k;
+        const pv_seq_ref &sq = a.st->blk.seq[sidx];
+        len = sq.st->len; gamma = sq.gamma; row0 = sq.row0; mp = z - sq.unit0;
+        pool = (const uint16_t *)sq.pool; gm.n_pages = sq.n_pages;
+        ph0 = sq.page_table[min((p0 >> 4) >> sub_shift, sq.n_pages - 1)]; ph1g = sq.page_table[min(((p0 >> 4) + 1) >> sub_shift, sq.n_pages - 1)];
+    }
+    const int nkeys = len + gamma;
     if (c * CK >= nkeys) return;
     const int nrows = a.group * gamma;
+    if (mp * 32 >= nrows) return;                      // (a unit beyond the sequence's rows: the grid is sized for the largest)
     const bool has_keys = p0 < nkeys;
     // this lane's query row: row lane%16 of the wave's 16-row tile
     const int m = mp * 32 + rt * 16 + jl;
@@ -92,16 +104,16 @@ __device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int mp, in
         const int g0 = p0 >> 4, g1 = two ? g0 + 1 : g0;
         const int ph1 = two ? ph1g : ph0;
         // a dead lane reads row 0 of the first head: its scores are masked below (lim = -1)
-        const size_t qoff = ((size_t)j * a.n_q_heads + kvh * a.group + al) * HD + g * 8;
+        const size_t qoff = ((size_t)(row0 + j) * a.n_q_heads + kvh * a.group + al) * HD + g * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             qh[ks] = *(const uint4 *)(a.q_hi + qoff + ks * 32);
             ql[ks] = *(const uint4 *)(a.q_lo + qoff + ks * 32);
         }
-        const uint16_t *kb0 = a.pool + pv_kv_block(gm, a.layer, ph0, kvh, 0) + (size_t)(g0 & sub_mask) * 16 * HD;
-        const uint16_t *kb1 = a.pool + pv_kv_block(gm, a.layer, ph1, kvh, 0) + (size_t)(g1 & sub_mask) * 16 * HD;
-        const uint16_t *vb0 = a.pool + pv_kv_block(gm, a.layer, ph0, kvh, 1) + (size_t)(g0 & sub_mask) * 16 * HD;
-        const uint16_t *vb1 = a.pool + pv_kv_block(gm, a.layer, ph1, kvh, 1) + (size_t)(g1 & sub_mask) * 16 * HD;
+        const uint16_t *kb0 = pool + pv_kv_block(gm, a.layer, ph0, kvh, 0) + (size_t)(g0 & sub_mask) * 16 * HD;
+        const uint16_t *kb1 = pool + pv_kv_block(gm, a.layer, ph1, kvh, 0) + (size_t)(g1 & sub_mask) * 16 * HD;
+        const uint16_t *vb0 = pool + pv_kv_block(gm, a.layer, ph0, kvh, 1) + (size_t)(g0 & sub_mask) * 16 * HD;
+        const uint16_t *vb1 = pool + pv_kv_block(gm, a.layer, ph1, kvh, 1) + (size_t)(g1 & sub_mask) * 16 * HD;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) { kt[0][ks] = ((const uint4 *)kb0)[ks * 64 + lane]; kt[1][ks] = ((const uint4 *)kb1)[ks * 64 + lane]; }
 #pragma unroll
@@ -171,7 +183,7 @@ __device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int mp, in
         *(float4 *)&sh_o[wave][jl][et * 16 + 4 * g] = make_float4(O[et][0] * f, O[et][1] * f, O[et][2] * f, O[et][3] * f);
     if (g == 0) sh_l[wave][jl] = lrow * f;
     __syncthreads();
-    const size_t unit = ((size_t)kvh * n_mp + mp) * a.max_chunks + c;
+    const size_t unit = ((size_t)kvh * n_units + z) * a.max_chunks + c;
     float *po = a.part_o + unit * 32 * HD;
     for (int i = threadIdx.x; i < TILES * 16 * (HD / 4); i += 512) {
         const int row = i / (HD / 4), c4 = i - row * (HD / 4), t = row >> 4, r = row & 15;
@@ -198,14 +210,21 @@ __device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int mp, in
 // (block row j, query head aq) unit, executed by NT threads (tid = 0..NT-1, all must call).
 // smem: NT + (NT / (HD/4)) * (HD/4) * 5 floats.
 template <int NB, int HD, int NT>
-__device__ inline void attn_merge_unit(const attn_args &a, int j, int aq, int mp_count, int tid, float *smem)
+__device__ inline void attn_merge_unit(const attn_args &a, int r, int aq, int n_units, int tid, float *smem)
 {
     constexpr int TPC = HD / 4;            // threads per chunk: 4 consecutive features each
     constexpr int NG = NT / TPC;           // chunk groups working side by side
-    const int gamma = a.st->gamma;
+    // block row r: its sequence's rows, length and first unit (a plain step: the cache itself)
+    const int nseq = a.st->blk.n_seq;
+    int gamma = a.st->gamma, len = a.st->len, row0 = 0, unit_s = 0;
+    if (nseq > 1) {
+        const pv_seq_ref &sq = a.st->blk.seq[a.st->rowseq[r]];
+        gamma = sq.gamma; len = sq.st->len; row0 = sq.row0; unit_s = sq.unit0;
+    }
+    const int j = r - row0;
     const int kvh = aq / a.group, al = aq - kvh * a.group, m = al * gamma + j, mp = m >> 5, row = m & 31;
-    const int nchunks = (a.st->len + gamma + (1 << a.chunk_shift) - 1) >> a.chunk_shift;
-    const size_t unit0 = ((size_t)kvh * mp_count + mp) * a.max_chunks;
+    const int nchunks = (len + gamma + (1 << a.chunk_shift) - 1) >> a.chunk_shift;
+    const size_t unit0 = ((size_t)kvh * n_units + unit_s + mp) * a.max_chunks;
     float *sh_m = smem;                                              // [NT]
     float (*sh_acc)[TPC][5] = (float (*)[TPC][5])(smem + NT);        // [NG][TPC][5]
     const int t = tid % TPC, cg = tid / TPC;
@@ -264,6 +283,6 @@ __device__ inline void attn_merge_unit(const attn_args &a, int j, int aq, int mp
     }
     const float inv = 1.0f / L;
     const float y[4] = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
-    store_operand4<NB>(a.xop_o, a.n_q_heads * HD, j, aq * HD + 4 * t, y);
+    store_operand4<NB>(a.xop_o, a.n_q_heads * HD, r, aq * HD + 4 * t, y);
 }
 

@@ -11,25 +11,52 @@
 // step modes written into pv_dev_state::mode
 enum { PV_MODE_VERIFY = 0, PV_MODE_PREFILL_LAST = 1, PV_MODE_PREFILL_MID = 2 };
 
+#define PV_MAX_SEQ 16           // sequences whose blocks one batched step may stack
+
+// One sequence of a block as the kernels see it.  A plain step has one (the cache itself); a batched
+// step (pv_verify_batch) stacks the blocks of several caches of one model into one pass over the
+// weights: rows row0 .. row0 + gamma - 1 of the stacked block belong to this sequence, their keys and
+// values live in this sequence's pages, their positions follow this sequence's length.
+struct pv_dev_state;
+struct pv_seq_ref {
+    pv_dev_state *st;           // the sequence's own state (len, pending; accepted / next_token on return)
+    void *pool;                 // its KV pages
+    const int32_t *page_table;
+    int32_t gamma, row0;
+    int32_t n_pages, unit0;     // pool geometry; first attention row-group unit of this sequence
+};
+struct pv_block_desc {          // which sequences the running block is made of
+    int32_t n_seq, pad;
+    pv_seq_ref seq[PV_MAX_SEQ];
+};
+
 // Per-cache state that lives in device memory so that a step needs no host-side patching:
-// every kernel reads the cache length and row count from here.
+// every kernel reads the cache length and row count from here.  For a batched step the state of
+// the first cache (the "leader") describes the block; len / pending / accepted / next_token stay
+// per sequence in each cache's own state.
 struct pv_dev_state {
     int32_t len;                // committed tokens
     int32_t pending;            // stage's own prediction for position len, -1 = unknown
-    int32_t gamma;              // rows of the running block
+    int32_t gamma;              // rows of the running block (all sequences together)
     int32_t mode;
     int32_t accepted, next_token;
     int32_t pad[2];
     int32_t draft[PV_MAX_ROWS];
     int32_t pred[PV_MAX_ROWS];
+    int32_t rowseq[PV_MAX_ROWS];    // sequence of each row and its absolute position (written by the block set-up)
+    int32_t rowpos[PV_MAX_ROWS];
+    pv_block_desc blk;
 };
 
 // pinned host mailbox (one per cache)
 struct pv_host_io {
     int32_t draft[PV_MAX_ROWS];
     int32_t hdr[4];             // len, pending, gamma, mode
-    int32_t result[4];          // written by the step's last kernel: accepted, next_token, error flag (a row without a finite logit)
+    int32_t result[2 * PV_MAX_SEQ + 2];   // written by the step's last kernel: (accepted, next_token) per sequence, then the error flag
+    pv_block_desc single;       // the one-sequence description of this cache (constant)
+    pv_block_desc batch;        // staging of a batched step's description
 };
+#define PV_RESULT_ERR (2 * PV_MAX_SEQ)
 
 struct pv_tensor_ref {
     size_t  off;                // byte offset in the weight arena
@@ -67,11 +94,13 @@ struct pv_cache {
     char *d_pool; size_t pool_bytes;
     char *d_ws; size_t ws_bytes;
     int32_t max_tokens, n_pages, rows_cap;
+    int32_t units_cap;          // attention row-group units the workspace's partial arrays hold
     pv_ws ws;
     pv_host_io *io;             // pinned host memory, mapped into the device's address space
     pv_host_io *d_io;           // the same mailbox as the kernels address it
     int32_t len, pending, last_rows;
     int32_t blk_start, blk_rows;   // positions the last block wrote K/V for (blk_rows = 0: none on record)
+    int32_t blk_units, blk_seq_rows; // batched step in the making: attention row-group units in all, most rows of one sequence (0: plain step)
     bool in_flight; hipStream_t flight_stream;
     // instrumentation: one kernel kind bracketed by events, one pair per layer
     int32_t prof_kind, prof_pending;
@@ -136,8 +165,9 @@ static inline bool pv_is_q4_kind(int kind)
     return kind == PV_T_WQ || kind == PV_T_WK || kind == PV_T_WV || kind == PV_T_WO || kind == PV_T_WG || kind == PV_T_WU ||
            kind == PV_T_WD || kind == PV_T_LM_HEAD;
 }
-size_t pv_mat_part_floats(const pv_model *m, int rows_cap, int max_tokens);
-size_t pv_attn_part_floats(const pv_model *m, int rows_cap, int max_tokens);
+size_t pv_mat_part_floats(const pv_model *m, int rows_cap, int units_cap, int max_tokens);
+size_t pv_attn_part_floats(const pv_model *m, int units_cap, int max_tokens);
+int pv_attn_units(const pv_model *m, int rows);              // attention row-group units of one sequence with `rows` rows
 int pv_mat_attention_init(int head_dim);
 int pv_mat_attention(pv_cache *c, int layer, int rows, float *part, uint16_t *xop_o, hipStream_t s);
 void pv_set_error(const char *fmt, ...);

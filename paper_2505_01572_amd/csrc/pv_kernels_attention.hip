@@ -11,39 +11,48 @@ k_attn(const attn_args a)
 
 template <int NB, int HD>
 __global__ void __launch_bounds__(256)
-k_attn_merge(const attn_args a, int mp_count)
+k_attn_merge(const attn_args a, int n_units)
 {
     __shared__ float smem[256 + (256 / (HD / 4)) * (HD / 4) * 5];
     if ((int)blockIdx.x >= a.st->gamma) return;
-    attn_merge_unit<NB, HD, 256>(a, blockIdx.x, blockIdx.y, mp_count, threadIdx.x, smem);
+    attn_merge_unit<NB, HD, 256>(a, blockIdx.x, blockIdx.y, n_units, threadIdx.x, smem);
 }
 
 // ------------------------------- host side ----------------------------------------
 
-size_t pv_attn_part_floats(const pv_model *m, int rows_cap, int max_tokens)
+// Row-group units (32 query rows of one kv head) of one sequence with `rows` block rows
+int pv_attn_units(const pv_model *m, int rows)
 {
-    const pv_model_config &f = m->cfg;
-    const int group = f.n_q_heads / f.n_kv_heads, mp = (group * rows_cap + 31) / 32, chunks = (max_tokens + 127) / 128;   // the finer of the two chunkings
-    return (size_t)f.n_kv_heads * mp * chunks * 32 * (f.head_dim + 2);
+    const int group = m->cfg.n_q_heads / m->cfg.n_kv_heads;
+    return (group * rows + 31) / 32;
 }
 
+size_t pv_attn_part_floats(const pv_model *m, int units_cap, int max_tokens)
+{
+    const pv_model_config &f = m->cfg;
+    const int chunks = (max_tokens + 127) / 128;   // the finer of the two chunkings
+    return (size_t)f.n_kv_heads * units_cap * chunks * 32 * (f.head_dim + 2);
+}
+
+// rows: rows of the block; a batched step also gives its unit count and the most rows any one sequence has
 template <int NB, int HD>
 static int launch(pv_cache *c, attn_args &a, int rows, hipStream_t s)
 {
     const pv_model_config &f = c->m->cfg;
-    const int nrows = a.group * rows, mp = (nrows + 31) / 32;
+    const int seq_rows = c->blk_units ? c->blk_seq_rows : rows;
+    const int nrows = a.group * seq_rows, units = c->blk_units ? c->blk_units : (nrows + 31) / 32;
     // up to 16 query rows per kv head: 256-key chunks, eight waves of 32 keys each; more rows:
     // 128-key chunks, the waves split into two 16-row tiles x four 32-key groups
     constexpr size_t lds = attn_smem_floats<HD>() * sizeof(float);
     if (nrows <= 16) {
         a.chunk_shift = 8; a.max_chunks = (c->max_tokens + 255) / 256;
-        k_attn<HD, 1><<<dim3(a.max_chunks, f.n_kv_heads, mp), 512, lds, s>>>(a);
+        k_attn<HD, 1><<<dim3(a.max_chunks, f.n_kv_heads, units), 512, lds, s>>>(a);
     } else {
         a.chunk_shift = 7; a.max_chunks = (c->max_tokens + 127) / 128;
-        k_attn<HD, 2><<<dim3(a.max_chunks, f.n_kv_heads, mp), 512, lds, s>>>(a);
+        k_attn<HD, 2><<<dim3(a.max_chunks, f.n_kv_heads, units), 512, lds, s>>>(a);
     }
     PV_HIP(hipGetLastError());
-    k_attn_merge<NB, HD><<<dim3(rows, f.n_q_heads), 256, 0, s>>>(a, mp);
+    k_attn_merge<NB, HD><<<dim3(rows, f.n_q_heads), 256, 0, s>>>(a, units);
     PV_HIP(hipGetLastError());
     return PV_OK;
 }
@@ -79,9 +88,8 @@ int pv_mat_attention(pv_cache *c, int layer, int rows, float *part, uint16_t *xo
     a.max_chunks = (c->max_tokens + 127) / 128;        // sizes the partial arrays; the launch sets the chunking in use
     a.chunk_shift = 7;
     a.scale = 1.0f / sqrtf((float)f.head_dim);
-    const int mp_cap = (a.group * c->rows_cap + 31) / 32;
     a.part_o = part;
-    a.part_ml = part + (size_t)f.n_kv_heads * mp_cap * a.max_chunks * 32 * f.head_dim;
+    a.part_ml = part + (size_t)f.n_kv_heads * c->units_cap * a.max_chunks * 32 * f.head_dim;
     a.xop_o = xop_o; a.n_pages = c->n_pages;
     const bool nb1 = rows <= 8;
     switch (f.head_dim) {

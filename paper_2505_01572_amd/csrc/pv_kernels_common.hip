@@ -17,7 +17,7 @@ k_begin(pv_dev_state *st, const int32_t *mailbox, int gamma, int mode, const ST 
     const int j = blockIdx.x;
     if (j == 0) {
         if ((int)threadIdx.x < gamma) st->draft[threadIdx.x] = mailbox[threadIdx.x];
-        if (threadIdx.x == 0) { st->gamma = gamma; st->mode = mode; }
+        if (threadIdx.x == 0) { st->gamma = gamma; st->mode = mode; st->blk.seq[0].gamma = gamma; }
     }
     float *xr = x + (size_t)j * d;
     if (j >= gamma) {                        // padding rows: keep them finite
@@ -112,7 +112,7 @@ k_argmax(pv_dev_state *st, const float *logits, int vocab)
 // error flag go straight to the cache's pinned host mailbox.
 // One workgroup of 16 waves: a row is scanned by 16 / (rows rounded up to a power of two) waves
 // (one wave takes up to four rows when there are more than 16), sixteen candidates per lane in
-// flight; thread 0 applies the rule after the barrier.
+// flight; after the barrier one thread per sequence of the block applies the rule.
 // ---------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024)
 k_finish(pv_dev_state *st, int32_t *result, const float *pv, const int32_t *pi, int strips, int gamma, int mode, int vocab)
@@ -156,29 +156,41 @@ k_finish(pv_dev_state *st, int32_t *result, const float *pv, const int32_t *pi, 
         if ((int)threadIdx.x < gamma) pred_s[threadIdx.x] = st->pred[threadIdx.x];
         __syncthreads();
     }
-    if (threadIdx.x != 0) return;
-    int n, next, err = 0;
-    if (mode == PV_MODE_PREFILL_MID) { n = gamma; next = -1; }
-    else {
-        // a row without a finite logit has no arg-max: the step reports an error and commits nothing
-        for (int j = 0; j < gamma; ++j) { if (pred_s[j] < 0 || pred_s[j] >= vocab) err = 1; st->pred[j] = pred_s[j]; }
-        if (err) { n = 0; next = st->pending; }
-        else if (mode == PV_MODE_PREFILL_LAST) { n = gamma; next = pred_s[gamma - 1]; }
+    // the rule, one thread per sequence of the block (a plain step has one: the cache itself)
+    __shared__ int err_s;
+    if (threadIdx.x == 0) err_s = 0;
+    __syncthreads();
+    const int nseq = st->blk.n_seq;
+    if ((int)threadIdx.x < nseq) {
+        const pv_seq_ref sq = st->blk.seq[threadIdx.x];
+        pv_dev_state *ps = sq.st;                    // the sequence's own state
+        const int g = sq.gamma, r0 = sq.row0;
+        int n, next, err = 0;
+        if (mode == PV_MODE_PREFILL_MID) { n = g; next = -1; }
         else {
-            n = 0;
-            while (n < gamma) {
-                const int expected = (n == 0) ? (st->pending >= 0 ? st->pending : st->draft[0]) : pred_s[n - 1];
-                if (st->draft[n] != expected) break;
-                ++n;
+            // a row without a finite logit has no arg-max: the step reports an error and commits nothing
+            for (int j = 0; j < g; ++j) { if (pred_s[r0 + j] < 0 || pred_s[r0 + j] >= vocab) err = 1; st->pred[r0 + j] = pred_s[r0 + j]; }
+            if (err) { n = 0; next = ps->pending; }
+            else if (mode == PV_MODE_PREFILL_LAST) { n = g; next = pred_s[r0 + g - 1]; }
+            else {
+                n = 0;
+                while (n < g) {
+                    const int expected = (n == 0) ? (ps->pending >= 0 ? ps->pending : st->draft[r0]) : pred_s[r0 + n - 1];
+                    if (st->draft[r0 + n] != expected) break;
+                    ++n;
+                }
+                next = (n >= 1) ? pred_s[r0 + n - 1] : ps->pending;
             }
-            next = (n >= 1) ? pred_s[n - 1] : st->pending;
         }
+        ps->accepted = n;
+        ps->next_token = next;
+        ps->pending = next;
+        ps->len += n;
+        result[2 * threadIdx.x] = n; result[2 * threadIdx.x + 1] = next;
+        if (err) err_s = 1;
     }
-    st->accepted = n;
-    st->next_token = next;
-    st->pending = next;
-    st->len += n;
-    result[0] = n; result[1] = next; result[2] = err;
+    __syncthreads();
+    if (threadIdx.x == 0) result[PV_RESULT_ERR] = err_s;
 }
 
 __global__ void k_set_state(pv_dev_state *st, int len, int pending)

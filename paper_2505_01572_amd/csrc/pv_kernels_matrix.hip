@@ -41,7 +41,7 @@ static inline size_t xop_elems(int K) { return (size_t)2 * (K / 32) * 512; }   /
 static inline int col_tiles(int rows) { return rows <= 16 ? 1 : rows <= 32 ? 2 : 4; }
 static const size_t TILE_PART_FLOATS = (size_t)6 << 20;   // 24 MiB: the K-slicing below stays under it (about 2048 strip x column-tile KiB per 256 workgroups)
 
-static size_t mat_ws_layout(const pv_model *m, int rows_cap, int max_tokens, float *base, mat_ws *w)
+static size_t mat_ws_layout(const pv_model *m, int rows_cap, int units_cap, int max_tokens, float *base, mat_ws *w)
 {
     const pv_model_config &f = m->cfg;
     const int qd = f.n_q_heads * f.head_dim;
@@ -57,12 +57,12 @@ static size_t mat_ws_layout(const pv_model *m, int rows_cap, int max_tokens, flo
     p = take(ctc * (size_t)f.d_model); if (w) w->ssq1 = p;
     p = take(ctc * (size_t)f.vocab); if (w) w->pmax_val = p;
     p = take(ctc * (size_t)f.vocab); if (w) w->pmax_idx = (int32_t *)p;
-    p = take(pv_attn_part_floats(m, rows_cap, max_tokens)); if (w) w->attn_part = p;
+    p = take(pv_attn_part_floats(m, units_cap, max_tokens)); if (w) w->attn_part = p;
     p = take(ctc >= 2 ? TILE_PART_FLOATS : 0); if (w) w->tile_part = p;
     return off;
 }
 
-size_t pv_mat_part_floats(const pv_model *m, int rows_cap, int max_tokens) { return mat_ws_layout(m, rows_cap, max_tokens, nullptr, nullptr); }
+size_t pv_mat_part_floats(const pv_model *m, int rows_cap, int units_cap, int max_tokens) { return mat_ws_layout(m, rows_cap, units_cap, max_tokens, nullptr, nullptr); }
 
 // ------------------------------------------------------------------------------------------
 // Weight repack: rows [row_begin, row_begin+row_count) of one tensor, row-major in staging,
@@ -162,9 +162,14 @@ k_mat_begin(pv_dev_state *st, const int32_t *mailbox, int rows, int mode, const 
             float *x, float *ssq, uint16_t *xop, float2 *rope, int d, int half)
 {
     const int lane = threadIdx.x, ct = blockIdx.y, j = ct * 16 + (lane & 15), g = lane >> 4, strip = blockIdx.x;
+    const int nseq = st->blk.n_seq;
+    // absolute position of block row r: the cache's length + r, or in a batched step the length of the
+    // row's sequence + the row's index inside that sequence's block
+    auto seq_of = [&](int r) { int sidx = 0; for (int k = 1; k < nseq; ++k) if (r >= st->blk.seq[k].row0) sidx = k; return sidx; };
+    auto pos_of = [&](int r) { if (nseq <= 1) return st->len + r; const pv_seq_ref &sq = st->blk.seq[seq_of(r)]; return sq.st->len + r - sq.row0; };
     if (blockIdx.x == 0 && ct == 0) {
-        for (int i = lane; i < rows; i += 64) st->draft[i] = mailbox[i];
-        if (lane == 0) { st->gamma = rows; st->mode = mode; }
+        for (int i = lane; i < rows; i += 64) { st->draft[i] = mailbox[i]; st->rowseq[i] = nseq <= 1 ? 0 : seq_of(i); st->rowpos[i] = pos_of(i); }
+        if (lane == 0) { st->gamma = rows; st->mode = mode; if (nseq <= 1) st->blk.seq[0].gamma = rows; }
     }
     float v[4] = {0.f, 0.f, 0.f, 0.f};
     if (j < rows) {
@@ -177,7 +182,7 @@ k_mat_begin(pv_dev_state *st, const int32_t *mailbox, int rows, int mode, const 
     for (int idx = blockIdx.x * 64 + lane; idx < rows * half; idx += gridDim.x * 64) {
         const int jj = idx / half, i = idx - jj * half;
         double sn, cs;
-        sincos((double)(st->len + jj) * inv_freq[i], &sn, &cs);
+        sincos((double)pos_of(jj) * inv_freq[i], &sn, &cs);
         rope[idx] = make_float2((float)cs, (float)sn);
     }
 }
@@ -814,7 +819,7 @@ static int run_block(pv_cache *c, hipStream_t s)
     const pv_model_config &f = m->cfg;
     const int rows = c->last_rows, d = f.d_model, hd = f.head_dim, qd = f.n_q_heads * hd, kvd = f.n_kv_heads * hd, F = f.ffn_dim;
     mat_ws mw;
-    mat_ws_layout(m, c->rows_cap, c->n_pages * f.page_tokens, c->ws.part, &mw);
+    mat_ws_layout(m, c->rows_cap, c->units_cap, c->n_pages * f.page_tokens, c->ws.part, &mw);
     const char *Wb = m->d_weights;
     auto gainp = [&](int kind, int l) { return (const uint16_t *)(Wb + pv_tref(m, kind, l).off); };
 
