@@ -84,7 +84,8 @@ typedef struct {
                            * the LM head are 4-bit codes with one bf16 scale per 32 input
                            * features, weight = (code - 8) * scale (the 4-bit target model of the
                            * paper's Sec. 4.1; format chosen by this library); needs PV_BF16, the
-                           * matrix path, input widths that are multiples of 128, max_gamma <= 16 */
+                           * matrix path, input widths that are multiples of 128; blocks of more than
+                           * 16 rows take one pass over the weights per 16 rows */
 } pv_model_config;
 
 #define PV_Q4_GROUP 32      /* input features per scale of a 4-bit matrix */
@@ -176,8 +177,8 @@ int pv_verify_wait(pv_cache *c, int32_t *accepted_len, int32_t *next_token);
  * because the weight and KV-cache loads are shared by all the tokens of a step; stacking the blocks
  * of independent sequences shares the weight loads further).  caches[0..n_seq): distinct caches of
  * one bf16 model on the matrix path, all created with the same max_tokens; sequence i contributes
- * gamma[i] draft tokens, draft = their concatenation (host arrays), sum of gamma[i] <= 64 (<= 16 with
- * 4-bit weights), n_seq <= 16.  Every sequence is verified exactly as pv_verify would verify it alone
+ * gamma[i] <= max_gamma draft tokens, draft = their concatenation (host arrays), sum of gamma[i] <= 64
+ * (<= max_gamma with 4-bit weights), n_seq <= 16.  Every sequence is verified exactly as pv_verify would verify it alone
  * (same rule, its own prefix_len guard, pending token, K/V pages and in-step rollback); on return
  * accepted_len[i] / next_token[i] hold its results.  The stacked activations use the workspace of
  * caches[0], whose pv_debug_logits then returns all rows in order.  Nothing is changed if a check fails.

@@ -62,7 +62,6 @@ static int check_config(const pv_model_config *c)
     if (c->weight_bits == 4) {
         if (path < PV_PATH_MATRIX || c->dtype != PV_BF16) { pv_set_error("4-bit weights need bf16 storage and the matrix path"); return PV_EINVAL; }
         if (c->d_model % 128 || c->ffn_dim % 128 || qd % 128) { pv_set_error("4-bit weights: d_model, ffn_dim, q_dim must be multiples of 128"); return PV_EINVAL; }
-        if (c->max_gamma > 16) { pv_set_error("4-bit weights: max_gamma must be <= 16"); return PV_EINVAL; }
     }
     if (path >= PV_PATH_MATRIX) {
         if (c->dtype != PV_BF16) { pv_set_error("matrix path needs bf16 storage"); return PV_EINVAL; }
@@ -283,7 +282,7 @@ static size_t layout_ws(const pv_model *m, int rows_cap, int units_cap, int n_pa
 // over the weights that 16-row chunks would).  The workspace is sized for it.
 static inline int prefill_rows_of(const pv_model *m)
 {
-    return (m->path >= PV_PATH_MATRIX && m->wbits != 4 && m->cfg.max_gamma < PV_MAX_ROWS) ? PV_MAX_ROWS : m->cfg.max_gamma;
+    return (m->path >= PV_PATH_MATRIX && m->wbits != 4 && m->cfg.max_gamma < PV_MAX_ROWS) ? PV_MAX_ROWS : m->cfg.max_gamma;   // (4-bit weights: wide blocks cost a pass over the weights per 16 rows, so a prompt goes in as max_gamma-row chunks)
 }
 static inline int rows_cap_of(const pv_model *m) { return (prefill_rows_of(m) + PV_ROW_PAD - 1) / PV_ROW_PAD * PV_ROW_PAD; }
 // a workspace's attention partials: one sequence of rows_cap rows, or a batch (every further sequence rounds its rows up to whole units)
@@ -712,7 +711,7 @@ extern "C" int pv_verify_batch(pv_cache *const *caches, int32_t n_seq, const int
         if ((rc = verify_checks(c, prefix_len[i], draft + rows, gamma[i])) != PV_OK) return rc;
         rows += gamma[i];
     }
-    if (rows > lead->rows_cap || (m->wbits == 4 && rows > 16)) { pv_set_error("%d rows in all: a step of this model takes at most %d", rows, m->wbits == 4 ? 16 : lead->rows_cap); return PV_ERANGE; }
+    if (rows > lead->rows_cap) { pv_set_error("%d rows in all: a step of this model takes at most %d", rows, lead->rows_cap); return PV_ERANGE; }
     for (int j = 0; j < rows; ++j)
         if (draft[j] < 0 || draft[j] >= m->cfg.vocab) { pv_set_error("token id %d at row %d outside [0, %d)", draft[j], j, m->cfg.vocab); return PV_ERANGE; }
     // the block's description: rows and attention row-group units of every sequence, in order

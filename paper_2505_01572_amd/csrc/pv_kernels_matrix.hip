@@ -273,7 +273,7 @@ k_gemm(const gemm_args a)
     else { const int per = (nbat + NW - 1) / NW; b = min(nbat, wave * per); bend = min(nbat, b + per); bstep = 1; }
     const size_t arr = (size_t)KT * 64;             // tiles of one strip = elements of one operand array, in uint4
     const uint4 *A = a.W + (size_t)strip0 * arr + lane;
-    const uint4 *B = a.xop + lane;                  // tile ct: hi at B + (2 ct) arr, lo at B + (2 ct + 1) arr   (NB == 2)
+    const uint4 *B = a.xop + lane + (size_t)(2 * a.ct0) * arr;   // tile ct: hi at B + (2 ct) arr, lo at B + (2 ct + 1) arr   (NB == 2); ct counts from a.ct0
     // a ragged last workgroup re-reads its first strip for the missing ones and drops the result
     size_t so[S];
 #pragma unroll
@@ -293,7 +293,7 @@ k_gemm(const gemm_args a)
     ssq_loads<(WB == 4 && NW <= 8) ? 16 / NW * 2 : 2> sl[CT];   // d up to 8192 without a serial tail of loads
     if (NORM) {
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+        for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)(a.ct0 + ct) * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
     }
 
     const size_t qstrip = (size_t)(KT / 4) * PV_Q4_BATCH;
@@ -357,12 +357,12 @@ k_gemm(const gemm_args a)
         qbatch q0, q1, q2;
         k_walk<DEPTH>(cnt, q0, q1, q2, issue, consume, [&]() {
             if (NORM) {
-                const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
+                const float4 s4 = ssq_finish(a.ssq + (size_t)a.ct0 * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][0][4 * lane] = s4;
             }
             if (PARK && wave < S) {
                 epi_pre pre;
-                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
+                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, a.ct0);
                 epi_park<EPI>(&pre_s[wave][lane], pre);
             }
         });
@@ -406,12 +406,12 @@ k_gemm(const gemm_args a)
         wbatch q0, q1, q2;
         k_walk<DP>(cnt, q0, q1, q2, issue, consume, [&]() {
             if (NORM) {
-                const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
+                const float4 s4 = ssq_finish(a.ssq + (size_t)a.ct0 * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][0][4 * lane] = s4;
             }
             if (PARK && wave < S) {
                 epi_pre pre;
-                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
+                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, a.ct0);
                 epi_park<EPI>(&pre_s[wave][lane], pre);
             }
         });
@@ -462,13 +462,13 @@ k_gemm(const gemm_args a)
         if (NORM) {
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
-                const float4 s4 = ssq_finish(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+                const float4 s4 = ssq_finish(a.ssq + (size_t)(a.ct0 + ct) * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][ct][4 * lane] = s4;
             }
         }
         if (PARK && wave < S) {                     // behind the first batch's loads, ahead of its use
             epi_pre pre;
-            epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
+            epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, a.ct0);
             epi_park<EPI>(&pre_s[wave][lane], pre);
         }
         if (first) { use_batch(); b += bstep; }
@@ -515,7 +515,7 @@ k_gemm(const gemm_args a)
         for (int w = 1; w < NW; ++w) { const f32x4 p = red[w][wave][ct][lane]; sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3]; }
         epi_pre pre;
         if (PARK) epi_unpark<EPI>(&pre_s[wave][lane], pre);
-        else epi_prefetch<EPI>(a, strip, lane, pre, ct);
+        else epi_prefetch<EPI>(a, strip, lane, pre, a.ct0 + ct);
         if (NORM) {
             float tot = ssq_s[0][ct][lane & 15];
 #pragma unroll
@@ -523,7 +523,7 @@ k_gemm(const gemm_args a)
             pre.rj = 1.0f / sqrtf(tot * a.inv_d + a.eps);
         }
         if (hslot && (lane >> 5) != hsel) pre.rows = 0;           // features 4 (lane / 16) .. + 3 of the other half: nothing to store
-        epi_apply<NB, EPI>(a, strip, lane, sum, pre, ct);
+        epi_apply<NB, EPI>(a, strip, lane, sum, pre, a.ct0 + ct);
     }
 }
 
@@ -727,7 +727,15 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
             else if (g.ktiles >= 64) k_gemm<NB, 1, 1, EPI, 16, 4><<<strips, 1024, 0, s>>>(ga);
             else k_gemm<NB, 1, 1, EPI, 8, 4><<<strips, 512, 0, s>>>(ga);
         } else {
-            pv_set_error("4-bit weights: at most 16 rows per block"); return PV_ERANGE;
+            // 4-bit weights, 17..64 rows: the 16-row kernel once per column tile (the weights are streamed
+            // CT times; at 4.5 bits per weight that is about what one pass over 16-bit weights moves)
+            for (int ct = 0; ct < CT; ++ct) {
+                gemm_args gc = g;
+                gc.ct0 = ct;
+                const int rc = launch_gemm<2, 1, EPI>(m, gc, strips, s);
+                if (rc != PV_OK) return rc;
+            }
+            return PV_OK;
         }
     } else if constexpr (NB == 2) {
         // Strips per workgroup: with enough strips to fill the machine anyway, the 2 CT operand

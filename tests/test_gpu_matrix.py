@@ -82,11 +82,11 @@ def test_matrix_path_matches_oracle(pvlib, shape, path):
     _check_against_oracle(pvlib, shape, path, 16, 37, (8, 13, 1, 5, 16, 3), 96)   # prefill chunks of 16, 16, 5 rows
 
 
-@pytest.mark.parametrize("shape", [MAT_A, MAT_C, FUSE_A], ids=lambda v: v.name)
-def test_wide_blocks_match_oracle(pvlib, shape):
-    """Blocks of 17..64 rows (two and four 16-row column tiles per weight pass), next to narrow
-    ones on the same cache; the prompt is prefilled in 64-row chunks plus a ragged rest."""
-    _check_against_oracle(pvlib, shape, 0, 64, 100, (32, 17, 64, 8, 40, 1, 33), 320)
+def test_wide_blocks_match_oracle(pvlib, wide_shape):
+    """Blocks of 17..64 rows (two and four 16-row column tiles per weight pass; with 4-bit weights one
+    weight pass per column tile), next to narrow ones on the same cache; the prompt is prefilled in
+    64-row chunks plus a ragged rest."""
+    _check_against_oracle(pvlib, wide_shape, 0, 64, 100, (32, 17, 64, 8, 40, 1, 33), 320)
 
 
 LONG_A = pv_inputs.ModelShape("long_a", 1, 128, 8, 2, 32, 352, 512, rope_base=500000.0, dtype="bf16", seed=5757)
@@ -212,6 +212,11 @@ Q4_C = pv_inputs.ModelShape("q4_c", 2, 512, 8, 8, 64, 1408, 1008, dtype="bf16", 
 Q4_D = pv_inputs.ModelShape("q4_d", 2, 2176, 8, 2, 128, 4096, 16384, rope_base=500000.0, dtype="bf16", seed=7474, weight_bits=4)
 
 
+@pytest.fixture(params=["mat_a", "mat_c", "fuse_a", "q4_a", "q4_c"])
+def wide_shape(request):
+    return {"mat_a": MAT_A, "mat_c": MAT_C, "fuse_a": FUSE_A, "q4_a": Q4_A, "q4_c": Q4_C}[request.param]
+
+
 @pytest.mark.parametrize("shape", [Q4_A, Q4_B, Q4_C, Q4_D], ids=lambda v: v.name)
 def test_q4_weights_match_oracle(pvlib, shape):
     """The oracle runs the same decoder on the dequantised weights (code - 8) * scale; the library
@@ -229,5 +234,4 @@ def test_q4_model_is_smaller_and_rejects_plain_loads(pvlib):
         m4.load_weights("wq", 0, 0, rows)                   # a 4-bit matrix does not take bf16 rows
     with pytest.raises(pv.PVError):
         m16.load_weights_q4("wq", 0, 0, np.zeros((16, Q4_B.d_model // 2), np.uint8), np.zeros((16, Q4_B.d_model // 32), np.uint16))
-    with pytest.raises(pv.PVError):
-        pv.Model(Q4_B, max_gamma=32)                        # wide blocks are not built for 4-bit weights
+    pv.Model(Q4_B, max_gamma=64)                            # wide blocks: one weight pass per 16-row column tile
