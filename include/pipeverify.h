@@ -93,7 +93,10 @@ typedef struct {
 typedef struct pv_model pv_model;   /* immutable once all weights are loaded */
 typedef struct pv_cache pv_cache;   /* one sequence of one stage             */
 
-/* ---- sizes: the caller allocates all device memory ---- */
+/* ---- sizes: the caller allocates all device memory ----
+ * (The paper runs stock LLaMA-2 / LLaMA-3 checkpoints, Sec. 4.1, and is silent on memory layout,
+ * loading and cache management: everything from here to pv_cache_set_page_table is this library's
+ * own design around the public LLaMA decoder definition.) */
 
 /* weight_bytes: device arena for all weights (+ small tables).  staging_bytes: device scratch
  * used only while pv_load_weights runs (may be freed after the last load has completed). */
@@ -111,7 +114,8 @@ int pv_model_create(const pv_model_config *cfg, void *d_weights, size_t weight_b
 void pv_model_destroy(pv_model *m);
 
 /*
- * Hand over rows [row_begin, row_begin + row_count) of one tensor.  host_rows points at the
+ * Hand over rows [row_begin, row_begin + row_count) of one tensor (the stage's model M_i of Sec. 3.2;
+ * the paper says nothing on how weights reach the device).  host_rows points at the
  * first of those rows (row-major, storage type of the model).  May be called many times per
  * tensor so that the host never holds a whole model; the chunks of a tensor come in row order
  * (row_begin = the end of the previous chunk, or 0 to start the tensor over; anything else is
@@ -131,8 +135,9 @@ int pv_load_weights(pv_model *m, int32_t kind, int32_t layer, int64_t row_begin,
 int pv_load_weights_q4(pv_model *m, int32_t kind, int32_t layer, int64_t row_begin, int64_t row_count,
                        const void *host_codes, const void *host_scales, void *hip_stream);
 
-/* d_page_pool / d_workspace: device, 256-byte aligned.  The new cache is empty (length 0,
- * pending unknown) with the identity page table. */
+/* The stage's key/value cache (Sec. 2.1: keys and values of the committed tokens are kept so that a
+ * step only computes its new positions), paged.  d_page_pool / d_workspace: device, 256-byte aligned.
+ * The new cache is empty (length 0, pending unknown) with the identity page table. */
 int pv_cache_create(const pv_model *m, void *d_page_pool, size_t page_pool_bytes,
                     void *d_workspace, size_t workspace_bytes, int32_t max_tokens, pv_cache **out);
 void pv_cache_destroy(pv_cache *c);
@@ -144,7 +149,8 @@ int pv_cache_set_page_table(pv_cache *c, const int32_t *phys_pages, int32_t n_pa
 /* ---- the step ---- */
 
 /*
- * Append n prompt tokens (host array), all accepted, in chunks of at most max_gamma rows
+ * The prefill phase of Sec. 2.1 (the prompt is processed in parallel before decoding starts):
+ * append n prompt tokens (host array), all accepted, in chunks of at most max_gamma rows
  * (matrix path with 16-bit weights: of up to 64 rows, whatever max_gamma is).
  * Afterwards length += n and pending = the stage's greedy token after the prompt.
  * Synchronises hip_stream before returning.

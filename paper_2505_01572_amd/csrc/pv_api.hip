@@ -316,10 +316,10 @@ extern "C" int pv_cache_create(const pv_model *m, void *d_page_pool, size_t page
     c->max_tokens = max_tokens; c->n_pages = (max_tokens + m->cfg.page_tokens - 1) / m->cfg.page_tokens;
     c->rows_cap = rows_cap_of(m); c->units_cap = units_cap_of(m);
     layout_ws(m, c->rows_cap, c->units_cap, c->n_pages, &c->ws, c->d_ws);
-    c->len = 0; c->pending = -1; c->last_rows = 0; c->blk_start = 0; c->blk_rows = 0; c->blk_units = 0; c->blk_seq_rows = 0; c->in_flight = false; c->flight_stream = nullptr; c->io = nullptr;
+    c->len = 0; c->pending = -1; c->last_rows = 0; c->blk_start = 0; c->blk_rows = 0; c->blk_units = 0; c->blk_seq_rows = 0; c->attn_keys = 0; c->in_flight = false; c->flight_stream = nullptr; c->io = nullptr;
     c->prof_kind = PV_PROF_NONE; c->prof_pending = 0; c->prof_ev = nullptr; c->prof_ms = 0; c->prof_launches = 0;
     c->use_graphs = true; c->cap_stream = nullptr;
-    for (auto &row : c->gexec) for (auto &ge : row) ge = nullptr;
+    for (auto &row : c->gexec) for (auto &md : row) for (auto &ge : md) ge = nullptr;
     if (hipHostMalloc((void **)&c->io, sizeof(pv_host_io), hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) {
         pv_set_error("hipHostMalloc failed"); delete c; return PV_EHIP;
     }
@@ -351,7 +351,7 @@ extern "C" void pv_cache_destroy(pv_cache *c)
 {
     if (!c) return;
     if (c->io) (void)hipHostFree(c->io);
-    for (auto &row : c->gexec) for (auto &ge : row) if (ge) (void)hipGraphExecDestroy(ge);
+    for (auto &row : c->gexec) for (auto &md : row) for (auto &ge : md) if (ge) (void)hipGraphExecDestroy(ge);
     if (c->cap_stream) (void)hipStreamDestroy(c->cap_stream);
     if (c->prof_ev) {
         for (int i = 0; i < 2 * c->m->cfg.n_layers; ++i) (void)hipEventDestroy(c->prof_ev[i]);
@@ -400,8 +400,13 @@ static int enqueue_block(pv_cache *c, const int32_t *tokens, int rows, int mode,
     // The launch sequence depends on (rows, mode) only: everything else a kernel needs (length,
     // pending token, draft ids) it reads from device memory.  So the sequence is recorded once
     // per (rows, mode) as a HIP graph and replayed; instrumented steps run the plain launches.
+    c->attn_keys = c->len + rows;
     if (c->use_graphs && c->prof_kind == PV_PROF_NONE) {
-        hipGraphExec_t &ge = c->gexec[rows][mode];
+        // a recorded step serves every length up to the next power of two: its attention grid is sized for that
+        int bucket = 8;
+        while ((1 << bucket) < c->len + rows && bucket < 30) ++bucket;
+        c->attn_keys = 1 << bucket;
+        hipGraphExec_t &ge = c->gexec[rows][mode][bucket - 8];
         if (!ge) {
             if (!c->cap_stream) PV_HIP(hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking));
             PV_HIP(hipStreamBeginCapture(c->cap_stream, hipStreamCaptureModeThreadLocal));
@@ -660,6 +665,7 @@ extern "C" int pv_verify_async_static(pv_cache *c, int32_t prefix_len, const int
     c->io->hdr[2] = gamma; c->io->hdr[3] = PV_MODE_VERIFY;
     c->last_rows = gamma;
     c->blk_start = c->len; c->blk_rows = gamma;
+    c->attn_keys = c->len + gamma;
     rc = record_block(c, gamma, PV_MODE_VERIFY, s);      // plain launches: the kernels take the buffers as arguments
     c->ws = own; c->rows_cap = own_cap; c->units_cap = own_ucap;
     c->last_rows = 0;                                   // the block's logits are in the shared array: not kept for pv_debug_logits
@@ -734,6 +740,8 @@ extern "C" int pv_verify_batch(pv_cache *const *caches, int32_t n_seq, const int
     // description in, the step as plain launches, the cache's own one-sequence description back in
     PV_HIP(hipMemcpyAsync(&lead->ws.state->blk, &bd, sizeof(pv_block_desc), hipMemcpyHostToDevice, s));
     lead->last_rows = rows; lead->blk_units = units; lead->blk_seq_rows = seq_rows;
+    lead->attn_keys = 0;
+    for (int i = 0; i < n_seq; ++i) if (caches[i]->len + gamma[i] > lead->attn_keys) lead->attn_keys = caches[i]->len + gamma[i];
     rc = record_block(lead, rows, PV_MODE_VERIFY, s);
     lead->blk_units = 0; lead->blk_seq_rows = 0;
     const hipError_t e1 = hipMemcpyAsync(&lead->ws.state->blk, &lead->io->single, sizeof(pv_block_desc), hipMemcpyHostToDevice, s);

@@ -1,5 +1,5 @@
-// Fused epilogues of the streaming GEMMs, shared by the per-GEMM kernels and the fused step
-// kernel.  An epilogue runs in one wavefront that holds the complete 16-feature x 16-column
+// Fused epilogues of the streaming GEMMs, shared by the packed-row kernel, the shared-tile kernel
+// of the wide blocks and its finishing kernel.  An epilogue runs in one wavefront that holds the complete 16-feature x 16-column
 // accumulator of a strip: lane l has features 4*(l/16)+r (r = 0..3) of column l%16.
 #pragma once
 #include "pv_matrix_common.h"

@@ -6,6 +6,7 @@
 #include "pipeverify.h"
 
 #define PV_MAX_ROWS 64          // hard cap on rows per block (max_gamma)
+#define PV_KEY_BUCKETS 24       // attention grids of recorded steps are sized for the next power of two of (length + rows)
 #define PV_ROW_PAD 16           // activation buffers are padded to a multiple of this many rows
 
 // step modes written into pv_dev_state::mode
@@ -100,6 +101,7 @@ struct pv_cache {
     pv_host_io *d_io;           // the same mailbox as the kernels address it
     int32_t len, pending, last_rows;
     int32_t blk_start, blk_rows;   // positions the last block wrote K/V for (blk_rows = 0: none on record)
+    int32_t attn_keys;          // keys the attention launch of the step being enqueued has to cover (host-side bound: length + rows)
     int32_t blk_units, blk_seq_rows; // batched step in the making: attention row-group units in all, most rows of one sequence (0: plain step)
     bool in_flight; hipStream_t flight_stream;
     // instrumentation: one kernel kind bracketed by events, one pair per layer
@@ -109,7 +111,7 @@ struct pv_cache {
     // one instantiated HIP graph per (rows, mode) of the step's launch sequence, captured on first use
     bool use_graphs;
     hipStream_t cap_stream;     // private stream that only ever records
-    hipGraphExec_t gexec[PV_MAX_ROWS + 1][3];
+    hipGraphExec_t gexec[PV_MAX_ROWS + 1][3][PV_KEY_BUCKETS];   // ... and per power-of-two bucket of the keys attention covers
 };
 
 // bracket helper used by the kernel families: records the start/end event of slot `slot`

@@ -44,12 +44,14 @@ static int launch(pv_cache *c, attn_args &a, int rows, hipStream_t s)
     // up to 16 query rows per kv head: 256-key chunks, eight waves of 32 keys each; more rows:
     // 128-key chunks, the waves split into two 16-row tiles x four 32-key groups
     constexpr size_t lds = attn_smem_floats<HD>() * sizeof(float);
+    // chunks to launch: enough for the keys this step can reach (the host's bound), not for the whole cache
+    const int keys = c->attn_keys > 0 && c->attn_keys < c->max_tokens ? c->attn_keys : c->max_tokens;
     if (nrows <= 16) {
         a.chunk_shift = 8; a.max_chunks = (c->max_tokens + 255) / 256;
-        k_attn<HD, 1><<<dim3(a.max_chunks, f.n_kv_heads, units), 512, lds, s>>>(a);
+        k_attn<HD, 1><<<dim3((keys + 255) / 256, f.n_kv_heads, units), 512, lds, s>>>(a);
     } else {
         a.chunk_shift = 7; a.max_chunks = (c->max_tokens + 127) / 128;
-        k_attn<HD, 2><<<dim3(a.max_chunks, f.n_kv_heads, units), 512, lds, s>>>(a);
+        k_attn<HD, 2><<<dim3((keys + 127) / 128, f.n_kv_heads, units), 512, lds, s>>>(a);
     }
     PV_HIP(hipGetLastError());
     k_attn_merge<NB, HD><<<dim3(rows, f.n_q_heads), 256, 0, s>>>(a, units);
