@@ -292,6 +292,7 @@ extern "C" int pv_cache_bytes(const pv_model *m, int32_t max_tokens, size_t *pag
 {
     if (!m || !page_pool_bytes || !workspace_bytes) { pv_set_error("null pointer"); return PV_EINVAL; }
     if (max_tokens <= 0) { pv_set_error("max_tokens must be positive"); return PV_ERANGE; }
+    if ((max_tokens + m->cfg.page_tokens - 1) / m->cfg.page_tokens >= (1 << 26)) { pv_set_error("max_tokens %d: more than 2^26 pages", max_tokens); return PV_ERANGE; }
     const pv_model_config &c = m->cfg;
     const int n_pages = (max_tokens + c.page_tokens - 1) / c.page_tokens;
     *page_pool_bytes = align_up((size_t)c.n_layers * n_pages * c.n_kv_heads * 2 * c.page_tokens * c.head_dim * m->elt, 256);

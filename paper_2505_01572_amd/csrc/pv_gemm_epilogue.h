@@ -5,6 +5,7 @@
 #include "pv_matrix_common.h"
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
+#define PV_SEQ_TAG_SHIFT 26     // physical page numbers stay below 2^26; the bits above carry a row's sequence in a batched step
 
 struct gemm_args {
     const uint4 *W;             // tiled region, strip-major
@@ -92,8 +93,7 @@ __device__ inline float4 ssq_finish(const float *ssq, int parts, int tid, int nt
 // in LDS, so that after the reduction only arithmetic and stores remain.
 struct epi_pre {
     float rj;
-    int rows, pos, phys, npg;   // npg: pages of the pool the row's keys and values go to
-    uint16_t *pool;
+    int rows, pos, phys;        // phys: physical page of the row's position; bits 26.. = 1 + the row's sequence in a batched step (0: the cache itself)
     float4 xo;
     uint2 gn;
     float2 cs[4];
@@ -103,7 +103,7 @@ template <int EPI>
 __device__ inline void epi_prefetch(const gemm_args &a, int strip, int lane, epi_pre &p, int ct = 0)
 {
     const int j = ct * 16 + (lane & 15), g = lane >> 4;
-    p.rj = 1.f; p.pos = 0; p.phys = 0; p.npg = 0; p.pool = nullptr;
+    p.rj = 1.f; p.pos = 0; p.phys = 0;
     p.xo = make_float4(0.f, 0.f, 0.f, 0.f); p.gn = make_uint2(0u, 0u);
 #pragma unroll
     for (int r = 0; r < 4; ++r) p.cs[r] = make_float2(1.f, 0.f);
@@ -117,13 +117,14 @@ __device__ inline void epi_prefetch(const gemm_args &a, int strip, int lane, epi
         // position and pages of row j: the cache's own, or in a batched step those of the row's sequence
         const int nseq = a.st->blk.n_seq;
         const int32_t *pt = a.page_table;
-        p.pos = a.st->len + j; p.pool = a.pool; p.npg = a.geom.n_pages;
+        int tag = 0;
+        p.pos = a.st->len + j;
         if (nseq > 1 && j < p.rows) {
-            const pv_seq_ref &sq = a.st->blk.seq[a.st->rowseq[j]];
-            p.pos = a.st->rowpos[j]; pt = sq.page_table; p.pool = (uint16_t *)sq.pool; p.npg = sq.n_pages;
+            const int sidx = a.st->rowseq[j];
+            p.pos = a.st->rowpos[j]; pt = a.st->blk.seq[sidx].page_table; tag = (sidx + 1) << PV_SEQ_TAG_SHIFT;
         }
         if (j < p.rows) {
-            if (strip >= a.q_strips) p.phys = pt[p.pos >> a.geom.page_shift];
+            if (strip >= a.q_strips) p.phys = pt[p.pos >> a.geom.page_shift] | tag;
             if (strip < a.q_strips + a.k_strips) {
                 const int spH = a.geom.head_dim >> 4, tt = strip % spH, e = tt * 8 + 4 * (g >> 1);
 #pragma unroll
@@ -141,7 +142,7 @@ __device__ inline void epi_park(epi_pre *slot, const epi_pre &p)
     slot->rows = p.rows;
     if (EPI == EPI_RESID) { slot->xo = p.xo; slot->gn = p.gn; }
     if (EPI == EPI_QKV) {
-        slot->pos = p.pos; slot->phys = p.phys; slot->npg = p.npg; slot->pool = p.pool;
+        slot->pos = p.pos; slot->phys = p.phys;
 #pragma unroll
         for (int r = 0; r < 4; ++r) slot->cs[r] = p.cs[r];
     }
@@ -150,14 +151,14 @@ __device__ inline void epi_park(epi_pre *slot, const epi_pre &p)
 template <int EPI>
 __device__ inline void epi_unpark(const epi_pre *slot, epi_pre &p)
 {
-    p.rj = 1.f; p.pos = 0; p.phys = 0; p.npg = 0; p.pool = nullptr;
+    p.rj = 1.f; p.pos = 0; p.phys = 0;
     p.xo = make_float4(0.f, 0.f, 0.f, 0.f); p.gn = make_uint2(0u, 0u);
 #pragma unroll
     for (int r = 0; r < 4; ++r) p.cs[r] = make_float2(1.f, 0.f);
     p.rows = slot->rows;
     if (EPI == EPI_RESID) { p.xo = slot->xo; p.gn = slot->gn; }
     if (EPI == EPI_QKV) {
-        p.pos = slot->pos; p.phys = slot->phys; p.npg = slot->npg; p.pool = slot->pool;
+        p.pos = slot->pos; p.phys = slot->phys;
 #pragma unroll
         for (int r = 0; r < 4; ++r) p.cs[r] = slot->cs[r];
     }
@@ -179,8 +180,14 @@ __device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 
     }
 
     if (EPI == EPI_QKV) {
+        // the pages the row's keys and values go to: the cache's own, or (batched step) those of the row's sequence
         pv_kv_geom gm = a.geom;
-        gm.n_pages = p.npg;
+        uint16_t *pool = a.pool;
+        const int phys = p.phys & ((1 << PV_SEQ_TAG_SHIFT) - 1);
+        if (p.phys >> PV_SEQ_TAG_SHIFT) {
+            const pv_seq_ref &sq = a.st->blk.seq[(p.phys >> PV_SEQ_TAG_SHIFT) - 1];
+            pool = (uint16_t *)sq.pool; gm.n_pages = sq.n_pages;
+        }
         const int hd = gm.head_dim, half = hd >> 1, spH = hd >> 4;
         const int tok = p.pos & (gm.page_tokens - 1);
         if (strip < a.q_strips + a.k_strips) {
@@ -202,13 +209,13 @@ __device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 
                     *(uint2 *)(a.q_lo + qo) = make_uint2(ql[0] | ((uint32_t)ql[1] << 16), ql[2] | ((uint32_t)ql[3] << 16));
                 } else {
                     const int kvh = h - a.n_q_heads;
-                    uint16_t *kp = p.pool + pv_kv_block(gm, a.layer, p.phys, kvh, 0) + pv_k_off(gm, tok, e + side * half);
+                    uint16_t *kp = pool + pv_kv_block(gm, a.layer, phys, kvh, 0) + pv_k_off(gm, tok, e + side * half);
                     *(uint2 *)kp = make_uint2(bf16_rne(o[0]) | ((uint32_t)bf16_rne(o[1]) << 16), bf16_rne(o[2]) | ((uint32_t)bf16_rne(o[3]) << 16));
                 }
             }
         } else if (live) {
             const int sv = strip - a.q_strips - a.k_strips, kvh = sv / spH, e = (sv - kvh * spH) * 16 + 4 * g;
-            uint16_t *vp = p.pool + pv_kv_block(gm, a.layer, p.phys, kvh, 1);
+            uint16_t *vp = pool + pv_kv_block(gm, a.layer, phys, kvh, 1);
 #pragma unroll
             for (int r = 0; r < 4; ++r) vp[pv_v_off(gm, tok, e + r)] = bf16_rne(v[r]);
         }

@@ -259,6 +259,7 @@ k_gemm(const gemm_args a)
     static_assert(!HF || ((WB == 4 || DP > 1) && S >= 2), "half strips: walked batches");
     constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : (DP > 1 && (S >= 2 || NB == 2)) ? 2 : 4;   // tiles per batch (16-bit weights)
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
+    const int ct0 = NB == 2 ? a.ct0 : 0;             // first column tile of this launch (packed rows: always the one tile)
     constexpr bool PARK = (CT == 1);                 // epilogue inputs fetched early (by the wave that will run the strip's epilogue) and parked in LDS
     // HF: the workgroup owns S - 1 whole strips and one 8-feature half of a strip it shares with
     // its neighbour (strips a.half_base ...), so that a GEMM with (k + 1/2) x 256 strips puts the
@@ -273,7 +274,7 @@ k_gemm(const gemm_args a)
     else { const int per = (nbat + NW - 1) / NW; b = min(nbat, wave * per); bend = min(nbat, b + per); bstep = 1; }
     const size_t arr = (size_t)KT * 64;             // tiles of one strip = elements of one operand array, in uint4
     const uint4 *A = a.W + (size_t)strip0 * arr + lane;
-    const uint4 *B = a.xop + lane + (size_t)(2 * a.ct0) * arr;   // tile ct: hi at B + (2 ct) arr, lo at B + (2 ct + 1) arr   (NB == 2); ct counts from a.ct0
+    const uint4 *B = a.xop + lane + (size_t)(2 * ct0) * arr;   // tile ct: hi at B + (2 ct) arr, lo at B + (2 ct + 1) arr   (NB == 2); ct counts from ct0
     // a ragged last workgroup re-reads its first strip for the missing ones and drops the result
     size_t so[S];
 #pragma unroll
@@ -293,7 +294,7 @@ k_gemm(const gemm_args a)
     ssq_loads<(WB == 4 && NW <= 8) ? 16 / NW * 2 : 2> sl[CT];   // d up to 8192 without a serial tail of loads
     if (NORM) {
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)(a.ct0 + ct) * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+        for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)(ct0 + ct) * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
     }
 
     const size_t qstrip = (size_t)(KT / 4) * PV_Q4_BATCH;
@@ -357,12 +358,12 @@ k_gemm(const gemm_args a)
         qbatch q0, q1, q2;
         k_walk<DEPTH>(cnt, q0, q1, q2, issue, consume, [&]() {
             if (NORM) {
-                const float4 s4 = ssq_finish(a.ssq + (size_t)a.ct0 * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
+                const float4 s4 = ssq_finish(a.ssq + (size_t)ct0 * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][0][4 * lane] = s4;
             }
             if (PARK && wave < S) {
                 epi_pre pre;
-                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, a.ct0);
+                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, ct0);
                 epi_park<EPI>(&pre_s[wave][lane], pre);
             }
         });
@@ -406,12 +407,12 @@ k_gemm(const gemm_args a)
         wbatch q0, q1, q2;
         k_walk<DP>(cnt, q0, q1, q2, issue, consume, [&]() {
             if (NORM) {
-                const float4 s4 = ssq_finish(a.ssq + (size_t)a.ct0 * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
+                const float4 s4 = ssq_finish(a.ssq + (size_t)ct0 * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][0][4 * lane] = s4;
             }
             if (PARK && wave < S) {
                 epi_pre pre;
-                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, a.ct0);
+                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, ct0);
                 epi_park<EPI>(&pre_s[wave][lane], pre);
             }
         });
@@ -462,13 +463,13 @@ k_gemm(const gemm_args a)
         if (NORM) {
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
-                const float4 s4 = ssq_finish(a.ssq + (size_t)(a.ct0 + ct) * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+                const float4 s4 = ssq_finish(a.ssq + (size_t)(ct0 + ct) * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][ct][4 * lane] = s4;
             }
         }
         if (PARK && wave < S) {                     // behind the first batch's loads, ahead of its use
             epi_pre pre;
-            epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, a.ct0);
+            epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, ct0);
             epi_park<EPI>(&pre_s[wave][lane], pre);
         }
         if (first) { use_batch(); b += bstep; }
@@ -515,7 +516,7 @@ k_gemm(const gemm_args a)
         for (int w = 1; w < NW; ++w) { const f32x4 p = red[w][wave][ct][lane]; sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3]; }
         epi_pre pre;
         if (PARK) epi_unpark<EPI>(&pre_s[wave][lane], pre);
-        else epi_prefetch<EPI>(a, strip, lane, pre, a.ct0 + ct);
+        else epi_prefetch<EPI>(a, strip, lane, pre, ct0 + ct);
         if (NORM) {
             float tot = ssq_s[0][ct][lane & 15];
 #pragma unroll
@@ -523,7 +524,7 @@ k_gemm(const gemm_args a)
             pre.rj = 1.0f / sqrtf(tot * a.inv_d + a.eps);
         }
         if (hslot && (lane >> 5) != hsel) pre.rows = 0;           // features 4 (lane / 16) .. + 3 of the other half: nothing to store
-        epi_apply<NB, EPI>(a, strip, lane, sum, pre, a.ct0 + ct);
+        epi_apply<NB, EPI>(a, strip, lane, sum, pre, ct0 + ct);
     }
 }
 
