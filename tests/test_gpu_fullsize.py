@@ -93,7 +93,7 @@ def test_full_prefix_two_layers(pvlib, name, T0):
     assert np.abs(ge - re_).max() <= 2.0 ** -7 * np.abs(re_).max()
 
 
-@pytest.mark.parametrize("name,T0", [("8b", 300), ("70b", 200)])
+@pytest.mark.parametrize("name,T0", [("8b", 300), ("70b", 200), ("70b_q4", 200)])
 def test_full_width_wide_blocks_two_layers(pvlib, name, T0):
     """Blocks of 17..64 rows at full width (shared-tile GEMM: K cut over workgroups for the
     projections with few strips, one slice for gate/up and the vocabulary projection); the prompt
@@ -157,3 +157,56 @@ def test_full_configuration_properties(pvlib, name, T0):
     c.set_pending(first)
     assert c.verify(T0, G[:gamma]) == (gamma, G[gamma])
     assert np.array_equal(c.debug_logits(), blk)
+
+
+def test_full_configuration_batched_steps(pvlib):
+    """The 8B-shaped verifier at full depth: four sequences with prompts of their own, verified as one
+    stacked block (4 x gamma 8 = 32 rows, the configuration bench.py times as its batch point), against
+    the same blocks verified one sequence at a time by the library itself (the oracle comparison of the
+    batched path is tests/test_gpu_batch.py; the single-sequence path at this depth is checked against the
+    oracle's goldens).  Logits within 1e-2 x RMS of each other (different row counts take different GEMM
+    kernels; 32 layers of bf16-stored K/V), decisions identical wherever the margin is clear, K/V of the accepted rows identical up to
+    bf16 rounding-boundary flips."""
+    import bench
+    import gc
+    import torch
+    gc.collect(); torch.cuda.empty_cache()
+    shape = CONFIGS["8b"]
+    gm = bench.load_model(pvlib, pv_inputs, shape, 16)
+    T0s, gamma = (2048, 777, 1500, 64), 8
+    solo, batch = [], []
+    for i, T0 in enumerate(T0s):
+        prompt = pv_inputs.uniform_tokens(8800 + i, T0, shape.vocab)
+        a, b = pvlib.Cache(gm, 2048 + 64), pvlib.Cache(gm, 2048 + 64)
+        a.prefill(prompt); b.prefill(prompt)
+        assert a.state() == b.state()
+        solo.append(a); batch.append(b)
+    for step in range(3):
+        drafts, want, rows = [], [], []
+        for i, a in enumerate(solo):
+            d = pv_inputs.uniform_tokens(8900 + 10 * step + i, gamma, shape.vocab)
+            d[0] = a.pending
+            T = len(a)
+            n, nxt = a.verify(T, d)
+            lg, pred = a.debug_logits(), a.debug_pred()
+            drafts.append(d); want.append((T, n, nxt, pred)); rows.append(lg)
+        got = pvlib.verify_batch(batch, drafts)
+        lg_b, pred_b = batch[0].debug_logits(), batch[0].debug_pred()
+        r0 = 0
+        for i, (T, n, nxt, pred) in enumerate(want):
+            lg = rows[i]
+            scale = np.sqrt((lg.astype(np.float64) ** 2).mean(axis=1, keepdims=True))
+            err = float((np.abs(lg_b[r0:r0 + gamma] - lg) / scale).max())
+            assert err < 1e-2, (step, i, err)        # each side is within 3e-3..6e-3 of the oracle at this depth (the goldens)
+            srt = np.sort(lg, axis=1)
+            safe = (srt[:, -1] - srt[:, -2]) > 0.05
+            assert np.array_equal(pred_b[r0:r0 + gamma][safe], pred[safe])
+            if safe[: max(n, 1)].all():
+                assert got[i] == (n, nxt) and batch[i].state() == solo[i].state()
+            else:
+                solo[i].rollback(T); batch[i].rollback(T)
+                solo[i].set_pending(int(drafts[i][0])); batch[i].set_pending(int(drafts[i][0]))
+            r0 += gamma
+    for a, b in zip(solo, batch):
+        ea, eb = pv_inputs.bf16_bits_to_f32(a.export()), pv_inputs.bf16_bits_to_f32(b.export())
+        assert ea.shape == eb.shape and np.abs(ea - eb).max() <= 2.0 ** -6 * np.abs(ea).max()
