@@ -195,6 +195,24 @@ int pv_verify_batch(pv_cache *const *caches, int32_t n_seq, const int32_t *prefi
                     const int32_t *gamma, int32_t *accepted_len, int32_t *next_token, void *hip_stream);
 
 /*
+ * Verify a draft TREE instead of a draft chain (Sec. 2.2: tree-structured verification explores several
+ * candidate continuations in one step; the paper names it as orthogonal to, and combinable with, its
+ * pipeline).  tokens[0..n) / parent[0..n) (host arrays): node i carries draft token tokens[i] and hangs
+ * under node parent[i] < i, or under the committed prefix if parent[i] = -1; n <= 64.  One block forward
+ * in which every node attends to the prefix, its ancestors and itself, at rotary position
+ * prefix_len + depth.  Then the stage's own greedy path is followed: starting with expected = pending
+ * (unknown: the first root is trusted), the lowest-numbered child of the current node whose token equals
+ * `expected` is accepted, and `expected` becomes the stage's prediction after that child; the walk stops
+ * where no child matches.  *accepted_len = nodes on the path, *next_token = the prediction after the
+ * last of them (pending if none), path[0..accepted_len) (nullable) = their node numbers.  The cache then
+ * holds prefix ++ the path's tokens (their K/V moved to consecutive positions), pending = next_token:
+ * exactly the state pv_verify reaches when handed the path as a chain.  bf16 models on the matrix path.
+ * pv_cache_readmit is not available after this call.  Synchronises hip_stream.
+ */
+int pv_verify_tree(pv_cache *c, int32_t prefix_len, const int32_t *tokens, const int32_t *parent, int32_t n,
+                   int32_t *accepted_len, int32_t *next_token, int32_t *path, void *hip_stream);
+
+/*
  * pv_verify_async for callers that cannot allocate: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  Same step, same results through pv_verify_wait, but it
  * calls no allocating routine (no graph is instantiated, no stream or event is created) and the

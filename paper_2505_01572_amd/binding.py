@@ -34,7 +34,7 @@ EXPORTS = [
     "pv_cache_create", "pv_cache_destroy", "pv_cache_set_page_table", "pv_prefill", "pv_verify",
     "pv_verify_async", "pv_verify_wait", "pv_rollback", "pv_cache_len", "pv_cache_set_pending",
     "pv_debug_logits", "pv_debug_pred", "pv_cache_export", "pv_step_bytes", "pv_strerror", "pv_last_error",
-    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_calib_read", "pv_verify_async_static", "pv_verify_batch", "pv_cache_use_graphs", "pv_load_weights_q4",
+    "pv_profile_select", "pv_profile_read", "pv_cache_readmit", "pv_calib_copy", "pv_calib_read", "pv_verify_async_static", "pv_verify_batch", "pv_verify_tree", "pv_cache_use_graphs", "pv_load_weights_q4",
 ]
 
 _lib = None
@@ -65,6 +65,7 @@ def lib():
         L.pv_verify_async_static.argtypes = [vp, i32, vp, i32, vp]
         L.pv_verify_wait.argtypes = [vp, P(i32), P(i32)]
         L.pv_verify_batch.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+        L.pv_verify_tree.argtypes = [vp, i32, vp, vp, i32, P(i32), P(i32), vp, vp]
         L.pv_rollback.argtypes = [vp, i32, vp]
         L.pv_cache_readmit.argtypes = [vp, i32, i32, vp]
         L.pv_cache_len.argtypes = [vp, P(i32), P(i32)]
@@ -231,6 +232,19 @@ class Cache:
         a = np.ascontiguousarray(draft, dtype=np.int32)
         with self._dev():
             _check(self.L.pv_verify_async(self.h, prefix_len, a.ctypes.data, len(a), _stream_ptr(stream)), "pv_verify_async")
+
+    def verify_tree(self, prefix_len, tokens, parents, stream=None):
+        """A draft tree: tokens[i] hangs under node parents[i] (-1: under the prefix).  Returns
+        (accepted_len, next_token, path) with path = the accepted nodes in order."""
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        p = np.ascontiguousarray(parents, dtype=np.int32)
+        assert len(t) == len(p)
+        n, nxt = ctypes.c_int32(), ctypes.c_int32()
+        path = np.full(len(t), -1, dtype=np.int32)
+        with self._dev():
+            _check(self.L.pv_verify_tree(self.h, prefix_len, t.ctypes.data, p.ctypes.data, len(t), ctypes.byref(n), ctypes.byref(nxt),
+                                         path.ctypes.data, _stream_ptr(stream)), "pv_verify_tree")
+        return n.value, nxt.value, path[:n.value].copy()
 
     def verify_async_static(self, prefix_len, draft, stream=None):
         """The step without any allocation: per-step buffers in the library's fixed device array."""

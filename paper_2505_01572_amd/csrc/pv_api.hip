@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <stddef.h>
 #include <new>
 #include <mutex>
 #include "pv_kernels_common.h"
@@ -758,6 +759,46 @@ extern "C" int pv_verify_batch(pv_cache *const *caches, int32_t n_seq, const int
     }
     if (lead->io->result[PV_RESULT_ERR]) { pv_set_error("a row of the block has no finite logit (non-finite weights or activations)"); return PV_ENUMERIC; }
     return PV_OK;
+}
+
+// ---- a draft tree instead of a draft chain ----
+static_assert(offsetof(pv_host_io, parent) == sizeof(int32_t) * PV_MAX_ROWS, "the block set-up kernel finds the parents right behind the draft ids");
+
+extern "C" int pv_verify_tree(pv_cache *c, int32_t prefix_len, const int32_t *tokens, const int32_t *parent, int32_t n,
+                              int32_t *accepted_len, int32_t *next_token, int32_t *path, void *hip_stream)
+{
+    int rc = check_ready(c);
+    if (rc != PV_OK) return rc;
+    if (!tokens || !parent || !accepted_len || !next_token) { pv_set_error("null pointer"); return PV_EINVAL; }
+    const pv_model *m = c->m;
+    if (m->path < PV_PATH_MATRIX) { pv_set_error("draft trees run on the matrix path (bf16 models)"); return PV_EINVAL; }
+    if (c->prof_kind != PV_PROF_NONE) { pv_set_error("kernel instrumentation is switched on for this cache"); return PV_ESTATE; }
+    if (prefix_len != c->len) { pv_set_error("prefix_len %d != cache length %d", prefix_len, c->len); return PV_ESTATE; }
+    if (n < 1 || n > c->rows_cap || n > PV_MAX_ROWS) { pv_set_error("a draft tree has 1 .. %d nodes, got %d", c->rows_cap < PV_MAX_ROWS ? c->rows_cap : PV_MAX_ROWS, n); return PV_ERANGE; }
+    if (c->len + n > c->max_tokens) { pv_set_error("length %d + %d nodes exceeds max_tokens %d", c->len, n, c->max_tokens); return PV_ERANGE; }
+    for (int i = 0; i < n; ++i) {
+        if (tokens[i] < 0 || tokens[i] >= m->cfg.vocab) { pv_set_error("token id %d at node %d outside [0, %d)", tokens[i], i, m->cfg.vocab); return PV_ERANGE; }
+        if (parent[i] < -1 || parent[i] >= i) { pv_set_error("node %d: parent %d must be -1 or an earlier node", i, parent[i]); return PV_EINVAL; }
+    }
+    memcpy(c->io->draft, tokens, sizeof(int32_t) * n);
+    memcpy(c->io->parent, parent, sizeof(int32_t) * n);
+    c->io->hdr[2] = n; c->io->hdr[3] = PV_MODE_TREE;
+    c->last_rows = n; c->attn_keys = c->len + n;
+    hipStream_t s = (hipStream_t)hip_stream;
+    rc = record_block(c, n, PV_MODE_TREE, s);               // plain launches
+    if (rc == PV_OK) rc = pv_k_tree_compact(c, s);
+    const hipError_t e = hipStreamSynchronize(s);
+    if (rc != PV_OK) return rc;
+    if (e != hipSuccess) { pv_set_error("draft-tree step failed: %s", hipGetErrorString(e)); return PV_EHIP; }
+    c->blk_rows = 0;                                         // the rows off the path are gone: nothing to re-admit
+    rc = absorb_result(c);
+    *accepted_len = c->io->result[0];
+    *next_token = c->io->result[1];
+    if (path && rc == PV_OK) {
+        // the accepted rows, in order (device state -> host)
+        PV_HIP(hipMemcpy(path, c->ws.state->path, sizeof(int32_t) * (size_t)*accepted_len, hipMemcpyDeviceToHost));
+    }
+    return rc;
 }
 
 extern "C" int pv_rollback(pv_cache *c, int32_t new_len, void *hip_stream)

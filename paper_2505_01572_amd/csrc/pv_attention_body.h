@@ -24,7 +24,8 @@
 // Softmax weights use the hardware exponential (__expf, relative error ~1e-6 at these
 // arguments): they are rounded to 16 mantissa bits for the second product anyway.
 // Q arrives already split (the QKV projection's epilogue writes the two bf16 arrays).
-// The causal part only touches keys >= len: key p is visible to block row j iff p <= len + j.
+// The causal part only touches keys >= len: block row j sees the block slots its mask names (a chain:
+// keys up to len + j; a draft tree: its ancestors' slots and its own).
 #pragma once
 #include "pv_matrix_common.h"
 
@@ -95,7 +96,10 @@ __device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int z, int
     const int m = mp * 32 + rt * 16 + jl;
     const bool live = m < nrows;
     const int al = live ? m / gamma : 0, j = live ? m - al * gamma : 0;
-    const int lim = live ? len + j : -1;
+    // which keys the row may see: every committed position, and of the block's own slots (len + q) those its
+    // mask names (a chain: up to its own; a draft tree: its ancestors and itself); a dead lane sees nothing
+    const uint64_t vmask = live ? a.st->rowmask[row0 + j] : 0ull;
+    auto visible = [&](int p) { const int q = p - len; return live && (q < 0 || (q < 64 && ((vmask >> q) & 1ull))); };
     uint4 kt[2][KS], qh[KS], ql[KS];
     uint2 vt[2][ET];
     if (has_keys) {
@@ -103,7 +107,7 @@ __device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int z, int
         const bool two = p0 + 16 < nkeys;
         const int g0 = p0 >> 4, g1 = two ? g0 + 1 : g0;
         const int ph1 = two ? ph1g : ph0;
-        // a dead lane reads row 0 of the first head: its scores are masked below (lim = -1)
+        // a dead lane reads row 0 of the first head: its scores are masked below
         const size_t qoff = ((size_t)(row0 + j) * a.n_q_heads + kvh * a.group + al) * HD + g * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -142,8 +146,8 @@ __device__ inline void attn_chunk(const attn_args &a, int c, int kvh, int z, int
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int pa = p0 + 4 * g + r, pb = pa + 16;
-            sv[r] = (pa <= lim) ? s0[r] * a.scale : -INFINITY;
-            sv[4 + r] = (pb <= lim) ? s1[r] * a.scale : -INFINITY;
+            sv[r] = visible(pa) ? s0[r] * a.scale : -INFINITY;
+            sv[4 + r] = visible(pb) ? s1[r] * a.scale : -INFINITY;
             mx = fmaxf(mx, fmaxf(sv[r], sv[4 + r]));
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));

@@ -10,7 +10,8 @@
 #define PV_ROW_PAD 16           // activation buffers are padded to a multiple of this many rows
 
 // step modes written into pv_dev_state::mode
-enum { PV_MODE_VERIFY = 0, PV_MODE_PREFILL_LAST = 1, PV_MODE_PREFILL_MID = 2 };
+enum { PV_MODE_VERIFY = 0, PV_MODE_PREFILL_LAST = 1, PV_MODE_PREFILL_MID = 2, PV_MODE_TREE = 3 };
+#define PV_N_MODES 4
 
 #define PV_MAX_SEQ 16           // sequences whose blocks one batched step may stack
 
@@ -44,14 +45,19 @@ struct pv_dev_state {
     int32_t pad[2];
     int32_t draft[PV_MAX_ROWS];
     int32_t pred[PV_MAX_ROWS];
-    int32_t rowseq[PV_MAX_ROWS];    // sequence of each row and its absolute position (written by the block set-up)
+    int32_t rowseq[PV_MAX_ROWS];    // sequence of each row and the cache slot (absolute position) its K/V go to (written by the block set-up)
     int32_t rowpos[PV_MAX_ROWS];
+    uint64_t rowmask[PV_MAX_ROWS];  // which of its sequence's block slots a row may attend to: bit q = the slot at (sequence length + q).
+                                    // A chain: slots 0 .. the row's own; a draft tree: the row's ancestors and itself
+    int32_t parent[PV_MAX_ROWS];    // draft tree (PV_MODE_TREE): parent row of each row, -1 = a child of the committed prefix
+    int32_t path[PV_MAX_ROWS];      // ... and, on return, the rows of the accepted path in order
     pv_block_desc blk;
 };
 
 // pinned host mailbox (one per cache)
 struct pv_host_io {
     int32_t draft[PV_MAX_ROWS];
+    int32_t parent[PV_MAX_ROWS];   // draft tree: parent row of each row
     int32_t hdr[4];             // len, pending, gamma, mode
     int32_t result[2 * PV_MAX_SEQ + 2];   // written by the step's last kernel: (accepted, next_token) per sequence, then the error flag
     pv_block_desc single;       // the one-sequence description of this cache (constant)
@@ -111,7 +117,7 @@ struct pv_cache {
     // one instantiated HIP graph per (rows, mode) of the step's launch sequence, captured on first use
     bool use_graphs;
     hipStream_t cap_stream;     // private stream that only ever records
-    hipGraphExec_t gexec[PV_MAX_ROWS + 1][3][PV_KEY_BUCKETS];   // ... and per power-of-two bucket of the keys attention covers
+    hipGraphExec_t gexec[PV_MAX_ROWS + 1][PV_N_MODES][PV_KEY_BUCKETS];   // ... and per power-of-two bucket of the keys attention covers
 };
 
 // bracket helper used by the kernel families: records the start/end event of slot `slot`

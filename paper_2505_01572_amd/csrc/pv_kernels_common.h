@@ -20,5 +20,6 @@ int pv_k_begin(pv_cache *c, int rows_pad, hipStream_t s);
 int pv_k_rope_append(pv_cache *c, int layer, int rows, hipStream_t s);
 int pv_k_argmax(pv_cache *c, int rows, hipStream_t s);
 int pv_k_finish(pv_cache *c, int rows, const float *pmax_val, const int32_t *pmax_idx, int strips, hipStream_t s);
+int pv_k_tree_compact(pv_cache *c, hipStream_t s);
 int pv_k_set_state(pv_cache *c, int len, int pending, hipStream_t s);
 int pv_k_export(pv_cache *c, size_t e0, size_t n, void *d_out, hipStream_t s);

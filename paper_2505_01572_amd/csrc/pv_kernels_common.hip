@@ -172,6 +172,22 @@ k_finish(pv_dev_state *st, int32_t *result, const float *pv, const int32_t *pi, 
             for (int j = 0; j < g; ++j) { if (pred_s[r0 + j] < 0 || pred_s[r0 + j] >= vocab) err = 1; st->pred[r0 + j] = pred_s[r0 + j]; }
             if (err) { n = 0; next = ps->pending; }
             else if (mode == PV_MODE_PREFILL_LAST) { n = g; next = pred_s[r0 + g - 1]; }
+            else if (mode == PV_MODE_TREE) {
+                // Greedy walk down the draft tree: at every step the child (lowest row first) whose token is the one
+                // the stage itself predicts next is taken; its own prediction is then what its children must match.
+                // The rows of the path are left in st->path for the compaction of their keys and values.
+                int cur = -1, expected = ps->pending;
+                n = 0;
+                for (;;) {
+                    int pick = -1;
+                    for (int r = cur + 1; r < g && pick < 0; ++r)
+                        if (st->parent[r] == cur && (expected < 0 ? true : st->draft[r] == expected)) pick = r;     // (pending unknown: the first root is trusted)
+                    if (pick < 0) break;
+                    st->path[n++] = pick;
+                    cur = pick; expected = pred_s[pick];
+                }
+                next = (n >= 1) ? pred_s[cur] : ps->pending;
+            }
             else {
                 n = 0;
                 while (n < g) {
@@ -191,6 +207,32 @@ k_finish(pv_dev_state *st, int32_t *result, const float *pv, const int32_t *pi, 
     }
     __syncthreads();
     if (threadIdx.x == 0) result[PV_RESULT_ERR] = err_s;
+}
+
+// ---------------------------------------------------------------------------------------
+// After a draft-tree step: the accepted path's rows sit in the slots of their row numbers
+// (old length + path[d]); move their keys and values to the positions they now hold
+// (old length + d).  path[] is increasing and path[d] >= d, so going through d in order never
+// overwrites a row that is still to be moved.  One thread per (layer, K|V, kv head, feature).
+// ---------------------------------------------------------------------------------------
+template <typename ST>
+__global__ void __launch_bounds__(256)
+k_tree_compact(const pv_dev_state *st, const int32_t *page_table, ST *pool, pv_kv_geom g, int n_layers)
+{
+    const int kvd = g.n_kv_heads * g.head_dim;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)n_layers * 2 * kvd) return;
+    const int c = (int)(idx % kvd), which = (int)((idx / kvd) & 1), layer = (int)(idx / kvd / 2);
+    const int h = c / g.head_dim, e = c - h * g.head_dim;
+    const int n = st->accepted, len0 = st->len - n;          // (the finishing kernel has added n already)
+    for (int d = 0; d < n; ++d) {
+        const int src = len0 + st->path[d], dst = len0 + d;
+        if (src == dst) continue;
+        const ST *sb = pool + pv_kv_block(g, layer, page_table[src >> g.page_shift], h, which);
+        ST *db = pool + pv_kv_block(g, layer, page_table[dst >> g.page_shift], h, which);
+        const int ts = src & (g.page_tokens - 1), td = dst & (g.page_tokens - 1);
+        db[which ? pv_v_off(g, td, e) : pv_k_off(g, td, e)] = sb[which ? pv_v_off(g, ts, e) : pv_k_off(g, ts, e)];
+    }
 }
 
 __global__ void k_set_state(pv_dev_state *st, int len, int pending)
@@ -271,6 +313,19 @@ int pv_k_argmax(pv_cache *c, int rows, hipStream_t s)
 int pv_k_finish(pv_cache *c, int rows, const float *pmax_val, const int32_t *pmax_idx, int strips, hipStream_t s)
 {
     k_finish<<<1, 1024, 0, s>>>(c->ws.state, c->d_io->result, pmax_val, pmax_idx, strips, rows, c->io->hdr[3], c->m->cfg.vocab);
+    PV_HIP(hipGetLastError());
+    return PV_OK;
+}
+
+int pv_k_tree_compact(pv_cache *c, hipStream_t s)
+{
+    const pv_kv_geom g = pv_geom(c);
+    const size_t n = (size_t)c->m->cfg.n_layers * 2 * g.n_kv_heads * g.head_dim;
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    if (c->m->cfg.dtype == PV_BF16)
+        k_tree_compact<uint16_t><<<blocks, 256, 0, s>>>(c->ws.state, c->ws.page_table, (uint16_t *)c->d_pool, g, c->m->cfg.n_layers);
+    else
+        k_tree_compact<float><<<blocks, 256, 0, s>>>(c->ws.state, c->ws.page_table, (float *)c->d_pool, g, c->m->cfg.n_layers);
     PV_HIP(hipGetLastError());
     return PV_OK;
 }

@@ -163,12 +163,23 @@ k_mat_begin(pv_dev_state *st, const int32_t *mailbox, int rows, int mode, const 
 {
     const int lane = threadIdx.x, ct = blockIdx.y, j = ct * 16 + (lane & 15), g = lane >> 4, strip = blockIdx.x;
     const int nseq = st->blk.n_seq;
-    // absolute position of block row r: the cache's length + r, or in a batched step the length of the
-    // row's sequence + the row's index inside that sequence's block
+    const bool tree = mode == PV_MODE_TREE;
+    __shared__ int parent[PV_MAX_ROWS];               // draft tree: the parents follow the draft ids in the mailbox; one read each, then walked in LDS
+    if (tree) { parent[lane] = lane < rows ? mailbox[PV_MAX_ROWS + lane] : -1; __syncthreads(); }
+    // Cache slot of block row r: the cache's length + r, or in a batched step the length of the row's
+    // sequence + the row's index inside that sequence's block.  Its rotary position is the same, except in a
+    // draft tree, where a row sits at (length + its depth) whatever slot it is stored in.
     auto seq_of = [&](int r) { int sidx = 0; for (int k = 1; k < nseq; ++k) if (r >= st->blk.seq[k].row0) sidx = k; return sidx; };
-    auto pos_of = [&](int r) { if (nseq <= 1) return st->len + r; const pv_seq_ref &sq = st->blk.seq[seq_of(r)]; return sq.st->len + r - sq.row0; };
+    auto slot_of = [&](int r) { if (nseq <= 1) return st->len + r; const pv_seq_ref &sq = st->blk.seq[seq_of(r)]; return sq.st->len + r - sq.row0; };
+    auto depth_of = [&](int r) { int dpt = 0; for (int q = parent[r]; q >= 0 && dpt < PV_MAX_ROWS; q = parent[q]) ++dpt; return dpt; };
     if (blockIdx.x == 0 && ct == 0) {
-        for (int i = lane; i < rows; i += 64) { st->draft[i] = mailbox[i]; st->rowseq[i] = nseq <= 1 ? 0 : seq_of(i); st->rowpos[i] = pos_of(i); }
+        for (int i = lane; i < rows; i += 64) {
+            st->draft[i] = mailbox[i]; st->rowseq[i] = nseq <= 1 ? 0 : seq_of(i); st->rowpos[i] = slot_of(i);
+            uint64_t m;
+            if (tree) { m = 1ull << i; for (int q = parent[i], k = 0; q >= 0 && k < PV_MAX_ROWS; q = parent[q], ++k) m |= 1ull << q; st->parent[i] = parent[i]; }
+            else { const int jj = i - (nseq <= 1 ? 0 : st->blk.seq[seq_of(i)].row0); m = jj >= 63 ? ~0ull : (2ull << jj) - 1; }
+            st->rowmask[i] = m;
+        }
         if (lane == 0) { st->gamma = rows; st->mode = mode; if (nseq <= 1) st->blk.seq[0].gamma = rows; }
     }
     float v[4] = {0.f, 0.f, 0.f, 0.f};
@@ -182,7 +193,7 @@ k_mat_begin(pv_dev_state *st, const int32_t *mailbox, int rows, int mode, const 
     for (int idx = blockIdx.x * 64 + lane; idx < rows * half; idx += gridDim.x * 64) {
         const int jj = idx / half, i = idx - jj * half;
         double sn, cs;
-        sincos((double)pos_of(jj) * inv_freq[i], &sn, &cs);
+        sincos((double)(tree ? st->len + depth_of(jj) : slot_of(jj)) * inv_freq[i], &sn, &cs);
         rope[idx] = make_float2((float)cs, (float)sn);
     }
 }

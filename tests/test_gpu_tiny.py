@@ -229,3 +229,19 @@ def test_weight_chunks_must_come_in_row_order(pvlib):
     m.load_weights("wq", 0, 64, w[64:])
     c.prefill([1, 2, 3])
     assert c.state()[0] == 3
+
+
+def test_calibration_kernels_run_on_ragged_sizes(pvlib):
+    """The plain copy and read-stream kernels (yardsticks for counters and for the stream ceiling) on sizes that
+    do not divide into whole wave slices, and their argument checks."""
+    import torch
+    src = torch.arange(0, 3 * 1024 * 1024 + 48, dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    pvlib.calib_copy(dst, src)
+    sink = pvlib.calib_read(src)                      # whole buffer: slices + a ragged rest
+    pvlib.calib_read(src, nbytes=16 * 7, offset=32)    # smaller than one slice round: only the rest loop
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src) and int(sink.sum()) == 0
+    import ctypes
+    assert pvlib.lib().pv_calib_read(ctypes.c_void_p(src.data_ptr() + 8), 32, ctypes.c_void_p(sink.data_ptr()), None) == -1    # misaligned
+    assert pvlib.lib().pv_calib_read(ctypes.c_void_p(src.data_ptr()), 24, ctypes.c_void_p(sink.data_ptr()), None) == -1       # not a multiple of 16
