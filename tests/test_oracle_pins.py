@@ -196,6 +196,29 @@ def test_f32_oracle_build_close_to_f64():
     assert np.abs(s - l32).max() < 1e-5
 
 
+def test_bf16_cache_amplifies_arithmetic_differences_with_depth():
+    """Two runs of a deep model that differ only in rounding (the oracle in fp32 and in fp64) stay within fp32 rounding
+    of each other with an unrounded cache, but not with the bf16 one: a K/V element whose two values fall on different
+    sides of a rounding boundary is stored one bf16 step (0.4 %) apart, and that is noise on the layers above.  The
+    flip rate grows with the layer and the logits end up two orders of magnitude further apart: the reason why the
+    end-to-end bars of the deep shapes are wider than the arithmetic of either side, and grow with depth."""
+    deep = pv_inputs.ModelShape("deep_narrow", 40, 256, 4, 2, 64, 704, 2048, rope_base=500000.0, dtype="bf16", seed=4242)
+    T = 64
+    toks = pv_inputs.uniform_tokens(9, T + 8, deep.vocab)
+    out = {}
+    for store in (ref.KV_BF16, ref.KV_REAL):
+        for real in ("f64", "f32"):
+            c = ref.RefCache(ref_model(deep, real=real), T + 16, kv_store=store)
+            c.prefill(toks[:T])
+            out[(store, real)] = (c.export().astype(np.float64), c.forward_block(toks[T:]).astype(np.float64))
+    rms = np.sqrt((out[(ref.KV_REAL, "f64")][1] ** 2).mean(axis=1, keepdims=True))
+    plain = (np.abs(out[(ref.KV_REAL, "f64")][1] - out[(ref.KV_REAL, "f32")][1]) / rms).max()
+    bf = (np.abs(out[(ref.KV_BF16, "f64")][1] - out[(ref.KV_BF16, "f32")][1]) / rms).max()
+    flips = (out[(ref.KV_BF16, "f64")][0] != out[(ref.KV_BF16, "f32")][0]).mean(axis=(1, 2, 3))
+    assert plain < 1e-5 and 10 * plain < bf < 3e-2
+    assert flips[0] < 1e-3 and flips[:8].mean() < flips[16:24].mean() < flips[32:].mean() < 0.2
+
+
 def test_degenerate_model_without_mixing_is_a_bigram_table():
     """W_o = 0 and W_d = 0: logits = lm_head . rmsnorm(E[token]) regardless of context."""
     shape = GQA
