@@ -311,6 +311,7 @@ extern "C" int pv_cache_create(const pv_model *m, void *d_page_pool, size_t page
     if (rc != PV_OK) return rc;
     if (page_pool_bytes < need_p || workspace_bytes < need_w) { pv_set_error("pool %zu < %zu or workspace %zu < %zu", page_pool_bytes, need_p, workspace_bytes, need_w); return PV_ENOMEM; }
     if (m->path >= PV_PATH_MATRIX && (rc = pv_mat_attention_init(m->cfg.head_dim)) != PV_OK) return rc;
+    if (m->path >= PV_PATH_MATRIX && m->wbits == 4 && (rc = pv_mat_gemm_init()) != PV_OK) return rc;
     pv_cache *c = new (std::nothrow) pv_cache();
     if (!c) return PV_ENOMEM;
     c->m = m; c->d_pool = (char *)d_page_pool; c->pool_bytes = page_pool_bytes;

@@ -13,7 +13,6 @@ struct gemm_args {
     int ktiles;                 // K / 32
     int interleave;             // K assignment of the waves (see k_gemm)
     int half_base;              // first of the strips that two workgroups share half and half (k_gemm<..., HF>)
-    int ct0;                    // first 16-row column tile this launch works on (a wide block taken one column tile per launch)
     float *tile_part;           // scratch for the K-slice partial sums of k_gemm_tile
     int nstrips;                // strips of this GEMM (a workgroup may own several; the last one may be ragged)
     const pv_dev_state *st;

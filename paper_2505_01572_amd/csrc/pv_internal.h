@@ -177,6 +177,7 @@ size_t pv_mat_part_floats(const pv_model *m, int rows_cap, int units_cap, int ma
 size_t pv_attn_part_floats(const pv_model *m, int units_cap, int max_tokens);
 int pv_attn_units(const pv_model *m, int rows);              // attention row-group units of one sequence with `rows` rows
 int pv_mat_attention_init(int head_dim);
+int pv_mat_gemm_init(void);
 int pv_mat_attention(pv_cache *c, int layer, int rows, float *part, uint16_t *xop_o, hipStream_t s);
 void pv_set_error(const char *fmt, ...);
 

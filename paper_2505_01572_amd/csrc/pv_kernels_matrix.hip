@@ -270,7 +270,6 @@ k_gemm(const gemm_args a)
     static_assert(!HF || ((WB == 4 || DP > 1) && S >= 2), "half strips: walked batches");
     constexpr int U = (S * CT >= 16) ? 1 : (S * CT >= 4) ? 2 : (DP > 1 && (S >= 2 || NB == 2)) ? 2 : 4;   // tiles per batch (16-bit weights)
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
-    const int ct0 = NB == 2 ? a.ct0 : 0;             // first column tile of this launch (packed rows: always the one tile)
     constexpr bool PARK = (CT == 1);                 // epilogue inputs fetched early (by the wave that will run the strip's epilogue) and parked in LDS
     // HF: the workgroup owns S - 1 whole strips and one 8-feature half of a strip it shares with
     // its neighbour (strips a.half_base ...), so that a GEMM with (k + 1/2) x 256 strips puts the
@@ -285,7 +284,7 @@ k_gemm(const gemm_args a)
     else { const int per = (nbat + NW - 1) / NW; b = min(nbat, wave * per); bend = min(nbat, b + per); bstep = 1; }
     const size_t arr = (size_t)KT * 64;             // tiles of one strip = elements of one operand array, in uint4
     const uint4 *A = a.W + (size_t)strip0 * arr + lane;
-    const uint4 *B = a.xop + lane + (size_t)(2 * ct0) * arr;   // tile ct: hi at B + (2 ct) arr, lo at B + (2 ct + 1) arr   (NB == 2); ct counts from ct0
+    const uint4 *B = a.xop + lane;                    // tile ct: hi at B + (2 ct) arr, lo at B + (2 ct + 1) arr   (NB == 2)
     // a ragged last workgroup re-reads its first strip for the missing ones and drops the result
     size_t so[S];
 #pragma unroll
@@ -305,7 +304,7 @@ k_gemm(const gemm_args a)
     ssq_loads<(WB == 4 && NW <= 8) ? 16 / NW * 2 : 2> sl[CT];   // d up to 8192 without a serial tail of loads
     if (NORM) {
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)(ct0 + ct) * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+        for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
     }
 
     const size_t qstrip = (size_t)(KT / 4) * PV_Q4_BATCH;
@@ -369,12 +368,12 @@ k_gemm(const gemm_args a)
         qbatch q0, q1, q2;
         k_walk<DEPTH>(cnt, q0, q1, q2, issue, consume, [&]() {
             if (NORM) {
-                const float4 s4 = ssq_finish(a.ssq + (size_t)ct0 * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
+                const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][0][4 * lane] = s4;
             }
             if (PARK && wave < S) {
                 epi_pre pre;
-                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, ct0);
+                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
                 epi_park<EPI>(&pre_s[wave][lane], pre);
             }
         });
@@ -418,12 +417,12 @@ k_gemm(const gemm_args a)
         wbatch q0, q1, q2;
         k_walk<DP>(cnt, q0, q1, q2, issue, consume, [&]() {
             if (NORM) {
-                const float4 s4 = ssq_finish(a.ssq + (size_t)ct0 * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
+                const float4 s4 = ssq_finish(a.ssq, a.ssq_parts, threadIdx.x, NW * 64, sl[0]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][0][4 * lane] = s4;
             }
             if (PARK && wave < S) {
                 epi_pre pre;
-                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, ct0);
+                epi_prefetch<EPI>(a, (HF && wave == S - 1) ? hstrip : min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
                 epi_park<EPI>(&pre_s[wave][lane], pre);
             }
         });
@@ -474,13 +473,13 @@ k_gemm(const gemm_args a)
         if (NORM) {
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
-                const float4 s4 = ssq_finish(a.ssq + (size_t)(ct0 + ct) * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+                const float4 s4 = ssq_finish(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
                 if (lane < 4) *(float4 *)&ssq_s[wave][ct][4 * lane] = s4;
             }
         }
         if (PARK && wave < S) {                     // behind the first batch's loads, ahead of its use
             epi_pre pre;
-            epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, ct0);
+            epi_prefetch<EPI>(a, min(strip0 + wave, a.nstrips - 1), lane, pre, 0);
             epi_park<EPI>(&pre_s[wave][lane], pre);
         }
         if (first) { use_batch(); b += bstep; }
@@ -527,7 +526,7 @@ k_gemm(const gemm_args a)
         for (int w = 1; w < NW; ++w) { const f32x4 p = red[w][wave][ct][lane]; sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3]; }
         epi_pre pre;
         if (PARK) epi_unpark<EPI>(&pre_s[wave][lane], pre);
-        else epi_prefetch<EPI>(a, strip, lane, pre, ct0 + ct);
+        else epi_prefetch<EPI>(a, strip, lane, pre, ct);
         if (NORM) {
             float tot = ssq_s[0][ct][lane & 15];
 #pragma unroll
@@ -535,7 +534,7 @@ k_gemm(const gemm_args a)
             pre.rj = 1.0f / sqrtf(tot * a.inv_d + a.eps);
         }
         if (hslot && (lane >> 5) != hsel) pre.rows = 0;           // features 4 (lane / 16) .. + 3 of the other half: nothing to store
-        epi_apply<NB, EPI>(a, strip, lane, sum, pre, ct0 + ct);
+        epi_apply<NB, EPI>(a, strip, lane, sum, pre, ct);
     }
 }
 
@@ -669,6 +668,174 @@ k_gemm_tile(const gemm_args a, int tps, float4 *part)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// The same for 4-bit weights (17..64 rows): the 8 waves of a workgroup own two strips each and walk
+// the strips' batches (4 K-tiles of codes + scales, 1152 bytes) in step; the 8 CT activation tiles of
+// a step are fetched once per workgroup and shared through LDS (two buffers, one barrier per step).
+// Per weight byte a 4-bit strip needs 3.6 times the activation bytes of a 16-bit one, on the L2 -> CU
+// path as well as out of LDS: hence two strips per wave.  A step is long (72 MFMAs at 64 rows), so the
+// weights are loaded two steps ahead and the activation tiles one (their registers are free once they sit in LDS).
+// Arithmetic as in k_gemm<WB = 4>: a code c enters as the bf16 number 16 + c, the product is taken
+// transposed (activation rows x features) on top of -24 x (row sums), scaled per K-tile; the row sums
+// are the same for every strip and are taken once per workgroup by the wave that brings the tile in.
+// The accumulators are turned back through LDS before the epilogue (or before they are stored as a
+// K-slice's partial sums for k_tile_finish).
+// ------------------------------------------------------------------------------------------
+template <int CT, int EPI>
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_gemm_tile_q4(const gemm_args a, int bps, float4 *part)
+{
+    constexpr int NW = 8, S = 2, U = 4, TPS = U * CT * 2, NLD = TPS / NW;    // NLD = CT activation tiles per wave and step
+    static_assert(NLD * NW == TPS, "every wave loads the same number of activation tiles");
+    constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
+    extern __shared__ uint4 tile_lds[];                         // [2][TPS][64]
+    uint4 (*sa)[TPS][64] = (uint4 (*)[TPS][64])tile_lds;
+    __shared__ float ssq_s[NW][CT][16];
+    __shared__ f32x4 rs[2][TPS / 2][4];                         // per (K-tile, column tile) of a step: -24 x its rows' sums, rows 4 g .. 4 g + 3 at [g]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int NBAT = a.ktiles >> 2;                             // batches of a strip
+    const int b0 = blockIdx.y * bps, b1 = min(NBAT, b0 + bps), nsteps = b1 - b0;   // this slice (not empty: the launch sees to it)
+    const int rot = (int)((blockIdx.x * 5u + blockIdx.y * 3u) % (unsigned)nsteps);
+    const size_t arr = (size_t)a.ktiles * 64;
+    const int sw = (blockIdx.x * NW + wave) * S;                // the wave's first strip; strips past the end: the last one again, dropped below
+    const char *Aq0 = (const char *)a.W + (size_t)min(sw, a.nstrips - 1) * (size_t)NBAT * PV_Q4_BATCH;
+    const char *Aq1 = (const char *)a.W + (size_t)min(sw + 1, a.nstrips - 1) * (size_t)NBAT * PV_Q4_BATCH;
+    const uint4 *B = a.xop + lane;
+
+    ssq_loads<2> sl[CT];
+    if (NORM && part == nullptr) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) ssq_issue(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+    }
+    f32x4 acc0[CT], acc1[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) acc0[ct] = acc1[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    struct wslot { uint4 c0, c1; uint2 s0, s1; };               // a batch of either strip
+    static_assert(NLD == 2 || NLD == 4, "activation slots are spelled out");
+    struct xslot { uint4 a, b, c, d; };                         // (named members: an array here ends up in scratch memory)
+    auto batch_of = [&](int step) { int k = min(step, nsteps - 1) + rot; if (k >= nsteps) k -= nsteps; return b0 + k; };   // (a step past the end re-reads the last one)
+    auto issue_w = [&](wslot &q, int step) {
+        const size_t o = (size_t)batch_of(step) * PV_Q4_BATCH;
+        q.c0 = *(const uint4 *)(Aq0 + o + lane * 16);
+        q.c1 = *(const uint4 *)(Aq1 + o + lane * 16);
+        q.s0 = *(const uint2 *)(Aq0 + o + 1024 + (lane & 15) * 8);
+        q.s1 = *(const uint2 *)(Aq1 + o + 1024 + (lane & 15) * 8);
+        asm volatile("" ::: "memory");
+    };
+    auto issue_x = [&](xslot &q, int step) {                    // pair p = wave (+ 8) of the step: K-tile p / CT of the batch, column tile p % CT, hi and lo
+        const int bt = batch_of(step);
+        auto tile = [&](int p, int half) { const int u = p / CT, ct = p % CT; return B[(size_t)(2 * ct + half) * arr + (size_t)(bt * 4 + u) * 64]; };
+        q.a = tile(wave, 0); q.b = tile(wave, 1);
+        if (NLD == 4) { q.c = tile(wave + NW, 0); q.d = tile(wave + NW, 1); }
+        asm volatile("" ::: "memory");
+    };
+    const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
+    auto stage = [&](const xslot &x, int buf) {                 // the wave's tiles of the step into LDS, with -24 x the row sums of each hi + lo pair
+        const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+        sa[buf][2 * wave][lane] = x.a; sa[buf][2 * wave + 1][lane] = x.b;
+        const f32x4 ra = mfma16(x.b, neg24, mfma16(x.a, neg24, zero4));
+        if ((lane & 15) == 0) rs[buf][wave][lane >> 4] = ra;
+        if (NLD == 4) {
+            sa[buf][2 * (wave + NW)][lane] = x.c; sa[buf][2 * (wave + NW) + 1][lane] = x.d;
+            const f32x4 rc = mfma16(x.d, neg24, mfma16(x.c, neg24, zero4));
+            if ((lane & 15) == 0) rs[buf][wave + NW][lane >> 4] = rc;
+        }
+    };
+    uint32_t sixteen = 0x41804180u;                             // (in a vector register, so that mask-and-merge is one instruction)
+    asm volatile("" : "+v"(sixteen));
+    auto codes = [&](uint32_t cw) {                             // 8 codes of a dword as the bf16 numbers 16 + c, in operand order
+        auto pick = [&](uint32_t v) { uint32_t r; asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "s"(0x00780078u), "v"(sixteen)); return r; };
+        return make_uint4(pick(cw << 3), pick(cw >> 1), pick(cw >> 5), pick(cw >> 9));
+    };
+    auto scale = [](uint2 s2, int u) { const uint32_t w = (u & 2) ? s2.y : s2.x; return __uint_as_float((u & 1) ? (w & 0xFFFF0000u) : (w << 16)); };
+    // One (K-tile, column tile) pair after the other, software-pipelined by hand: the LDS reads of the next pair go out,
+    // then the four MFMAs of this pair, then the scaling of the previous pair's products (whose MFMAs are done by then);
+    // the scheduling fences keep that order, which the compiler would otherwise serialise (read, wait, multiply, wait, scale).
+    auto compute = [&](const wslot &w, int buf) {
+        uint4 hiN = sa[buf][0][lane], loN = sa[buf][1][lane], wa0, wa1;
+        f32x4 t0N = rs[buf][0][lane >> 4], pa, pb;
+        float sc0 = 0.f, sc1 = 0.f, ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+        for (int p = 0; p < U * CT; ++p) {
+            const int u = p / CT, ct = p % CT;
+            const uint4 hi = hiN, lo = loN;
+            const f32x4 T0 = t0N;
+            if (ct == 0) {
+                wa0 = codes(u == 0 ? w.c0.x : u == 1 ? w.c0.y : u == 2 ? w.c0.z : w.c0.w);
+                wa1 = codes(u == 0 ? w.c1.x : u == 1 ? w.c1.y : u == 2 ? w.c1.z : w.c1.w);
+                sc0 = scale(w.s0, u); sc1 = scale(w.s1, u);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (p + 1 < U * CT) { hiN = sa[buf][2 * p + 2][lane]; loN = sa[buf][2 * p + 3][lane]; t0N = rs[buf][p + 1][lane >> 4]; }
+            __builtin_amdgcn_sched_barrier(0);
+            f32x4 Ta = mfma16(hi, wa0, T0), Tb = mfma16(hi, wa1, T0);
+            Ta = mfma16(lo, wa0, Ta); Tb = mfma16(lo, wa1, Tb);
+            __builtin_amdgcn_sched_barrier(0);
+            if (p > 0) {
+                const int pc = (p - 1) % CT;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) { acc0[pc][r] = fmaf(ps0, pa[r], acc0[pc][r]); acc1[pc][r] = fmaf(ps1, pb[r], acc1[pc][r]); }
+            }
+            pa = Ta; pb = Tb; ps0 = sc0; ps1 = sc1;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { acc0[CT - 1][r] = fmaf(ps0, pa[r], acc0[CT - 1][r]); acc1[CT - 1][r] = fmaf(ps1, pb[r], acc1[CT - 1][r]); }
+    };
+    wslot wA, wB;
+    xslot x;
+    issue_w(wA, 0); issue_w(wB, 1);
+    if (NORM && part == nullptr) {                              // (their loads went out before the weights': no wait for those; the
+#pragma unroll                                                  //  registers are free again before the activation slot fills)
+        for (int ct = 0; ct < CT; ++ct) {
+            const float4 s4 = ssq_finish(a.ssq + (size_t)ct * a.ssq_parts * 16, a.ssq_parts, threadIdx.x, NW * 64, sl[ct]);
+            if (lane < 4) *(float4 *)&ssq_s[wave][ct][4 * lane] = s4;
+        }
+    }
+    issue_x(x, 0);
+    // every wave of the workgroup takes the same steps: the barriers match.  Buffer i & 1 is rewritten at step i + 2,
+    // behind the barrier of step i + 1, which every wave reaches with its reads of step i done.
+#define PV_Q4_STEP(W, I)                                                                     \
+    if (s0 + (I) < nsteps) { stage(x, (I) & 1); issue_x(x, s0 + (I) + 1); __syncthreads(); compute(W, (I) & 1); issue_w(W, s0 + (I) + 2); }
+    for (int s0 = 0; s0 < nsteps; s0 += 2) { PV_Q4_STEP(wA, 0) PV_Q4_STEP(wB, 1) }
+#undef PV_Q4_STEP
+    __syncthreads();                                            // the last step's tiles have been read; ssq_s of every wave
+    // an accumulator is (row 4 g + r, feature f) for lane (g, f); the epilogues take (feature 4 g' + r', row j) from
+    // lane (g', j): turned through the wave's own KiB of the tile buffer
+    float *rf = (float *)&sa[0][wave][0];
+    const int g = lane >> 4, f = lane & 15;
+    auto turn = [&](f32x4 &v) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) rf[((f >> 2) * 16 + 4 * g + r) * 4 + (f & 3)] = v[r];
+        const f32x4 t = ((const f32x4 *)rf)[lane];              // (a wave's LDS traffic stays in order: no barrier inside the wave)
+        v = t;
+    };
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) { turn(acc0[ct]); turn(acc1[ct]); }
+#pragma unroll
+    for (int si = 0; si < S; ++si) {
+        const int strip = sw + si;
+        if (strip >= a.nstrips) continue;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const f32x4 v = si == 0 ? acc0[ct] : acc1[ct];
+            if (part != nullptr) {
+                part[(((size_t)blockIdx.y * a.nstrips + strip) * CT + ct) * 64 + lane] = make_float4(v[0], v[1], v[2], v[3]);
+                continue;
+            }
+            epi_pre pre;
+            epi_prefetch<EPI>(a, strip, lane, pre, ct);
+            if (NORM) {
+                float tot = ssq_s[0][ct][lane & 15];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) tot += ssq_s[w][ct][lane & 15];
+                pre.rj = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+            }
+            epi_apply<2, EPI>(a, strip, lane, v, pre, ct);
+        }
+    }
+}
+
 // Adds the K-slices' partial sums of k_gemm_tile in slice order and runs the epilogue: one wave
 // per (strip, column tile), the four waves of a workgroup take four strips of column tile
 // blockIdx.y.  At most TILE_MAX_SLICES slices: their loads go out together.
@@ -710,6 +877,27 @@ k_tile_finish(const gemm_args a, const float4 *part, int slices)
 
 
 
+static constexpr size_t tile_q4_lds(int ct) { return (size_t)2 * 4 * ct * 2 * 64 * sizeof(uint4); }   // two buffers of 8 ct activation tiles
+
+template <int CT, int EPI>
+static int allow_tile_q4_lds()
+{
+    PV_HIP(hipFuncSetAttribute((const void *)k_gemm_tile_q4<CT, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)tile_q4_lds(CT)));
+    return PV_OK;
+}
+
+// once per device before the first launch (and outside any stream capture): the wide-block kernels for 4-bit
+// weights use more dynamic LDS than the default limit
+int pv_mat_gemm_init(void)
+{
+    int rc;
+    if ((rc = allow_tile_q4_lds<2, EPI_QKV>()) != PV_OK || (rc = allow_tile_q4_lds<2, EPI_RESID>()) != PV_OK ||
+        (rc = allow_tile_q4_lds<2, EPI_SWIGLU>()) != PV_OK || (rc = allow_tile_q4_lds<2, EPI_LMHEAD>()) != PV_OK ||
+        (rc = allow_tile_q4_lds<4, EPI_QKV>()) != PV_OK || (rc = allow_tile_q4_lds<4, EPI_RESID>()) != PV_OK ||
+        (rc = allow_tile_q4_lds<4, EPI_SWIGLU>()) != PV_OK || (rc = allow_tile_q4_lds<4, EPI_LMHEAD>()) != PV_OK) return rc;
+    return PV_OK;
+}
+
 template <int NB, int CT, int EPI>
 static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStream_t s)
 {
@@ -739,14 +927,17 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
             else if (g.ktiles >= 64) k_gemm<NB, 1, 1, EPI, 16, 4><<<strips, 1024, 0, s>>>(ga);
             else k_gemm<NB, 1, 1, EPI, 8, 4><<<strips, 512, 0, s>>>(ga);
         } else {
-            // 4-bit weights, 17..64 rows: the 16-row kernel once per column tile (the weights are streamed
-            // CT times; at 4.5 bits per weight that is about what one pass over 16-bit weights moves)
-            for (int ct = 0; ct < CT; ++ct) {
-                gemm_args gc = g;
-                gc.ct0 = ct;
-                const int rc = launch_gemm<2, 1, EPI>(m, gc, strips, s);
-                if (rc != PV_OK) return rc;
-            }
+            // 4-bit weights, 17..64 rows: activation tiles shared through LDS, two strips per wave, one workgroup per CU
+            // (256 registers a lane); few strips: cut along K so that about 256 workgroups run, as for 16-bit weights
+            const int nbat = g.ktiles / 4, ngroups = (strips + 15) / 16;
+            int slices = ngroups >= 192 ? 1 : min(TILE_MAX_SLICES, (256 + ngroups - 1) / ngroups);
+            int bps = max(4, (nbat + slices - 1) / slices);
+            slices = (nbat + bps - 1) / bps;
+            while (slices > 1 && (size_t)slices * strips * CT * 256 > TILE_PART_FLOATS) { bps += 1; slices = (nbat + bps - 1) / bps; }
+            float4 *part = slices > 1 ? (float4 *)g.tile_part : nullptr;
+            k_gemm_tile_q4<CT, EPI><<<dim3(ngroups, slices), 512, tile_q4_lds(CT), s>>>(ga, bps, part);
+            PV_HIP(hipGetLastError());
+            if (slices > 1) { k_tile_finish<CT, EPI><<<dim3((strips + 3) / 4, CT), 256, 0, s>>>(ga, part, slices); PV_HIP(hipGetLastError()); }
             return PV_OK;
         }
     } else if constexpr (NB == 2) {
