@@ -278,12 +278,12 @@ static size_t layout_ws(const pv_model *m, int rows_cap, int units_cap, int n_pa
     return off;
 }
 
-// Rows per prefill chunk: the widest block the kernels of this model have (the matrix path with
-// 16-bit weights: PV_MAX_ROWS whatever max_gamma is; a prompt then needs a quarter of the passes
-// over the weights that 16-row chunks would).  The workspace is sized for it.
+// Rows per prefill chunk: the widest block the kernels of this model have (the matrix path:
+// PV_MAX_ROWS whatever max_gamma is; a prompt then needs a quarter of the passes over the
+// weights that 16-row chunks would).  The workspace is sized for it.
 static inline int prefill_rows_of(const pv_model *m)
 {
-    return (m->path >= PV_PATH_MATRIX && m->wbits != 4 && m->cfg.max_gamma < PV_MAX_ROWS) ? PV_MAX_ROWS : m->cfg.max_gamma;   // (4-bit weights: wide blocks cost a pass over the weights per 16 rows, so a prompt goes in as max_gamma-row chunks)
+    return (m->path >= PV_PATH_MATRIX && m->cfg.max_gamma < PV_MAX_ROWS) ? PV_MAX_ROWS : m->cfg.max_gamma;
 }
 static inline int rows_cap_of(const pv_model *m) { return (prefill_rows_of(m) + PV_ROW_PAD - 1) / PV_ROW_PAD * PV_ROW_PAD; }
 // a workspace's attention partials: one sequence of rows_cap rows, or a batch (every further sequence rounds its rows up to whole units)

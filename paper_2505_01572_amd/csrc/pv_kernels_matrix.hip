@@ -39,7 +39,13 @@ struct mat_ws {                 // carved out of pv_ws::part
 
 static inline size_t xop_elems(int K) { return (size_t)2 * (K / 32) * 512; }   // hi and lo arrays of one 16-row column tile
 static inline int col_tiles(int rows) { return rows <= 16 ? 1 : rows <= 32 ? 2 : 4; }
-static const size_t TILE_PART_FLOATS = (size_t)6 << 20;   // 24 MiB: the K-slicing below stays under it (about 2048 strip x column-tile KiB per 256 workgroups)
+// K-slice partial sums of the shared-tile GEMMs: slices x strips x column tiles KiB.  The launches cut a GEMM of fewer than
+// 192 workgroups into at most 16 slices and about 256 workgroups in all, which bounds slices x strips by 16 x 256 + 16 x 191
+// (16 strips per workgroup; fewer with 8), i.e. under 2 Mi floats per column tile; 24 MiB in all, which the launches stay under.
+static const size_t TILE_PART_FLOATS = (size_t)6 << 20;
+static inline size_t tile_part_floats(int col_tiles) { return std::min(TILE_PART_FLOATS, (size_t)col_tiles << 21); }
+// blocks that use those kernels: more than 16 rows, or any block of more than 8 rows with 4-bit weights
+static inline bool tile_part_needed(const pv_model *m, int col_tiles) { return col_tiles >= 2 || m->wbits == 4; }
 
 static size_t mat_ws_layout(const pv_model *m, int rows_cap, int units_cap, int max_tokens, float *base, mat_ws *w)
 {
@@ -58,7 +64,8 @@ static size_t mat_ws_layout(const pv_model *m, int rows_cap, int units_cap, int 
     p = take(ctc * (size_t)f.vocab); if (w) w->pmax_val = p;
     p = take(ctc * (size_t)f.vocab); if (w) w->pmax_idx = (int32_t *)p;
     p = take(pv_attn_part_floats(m, units_cap, max_tokens)); if (w) w->attn_part = p;
-    p = take(ctc >= 2 ? TILE_PART_FLOATS : 0); if (w) w->tile_part = p;
+    const size_t tp = tile_part_needed(m, (int)ctc) ? tile_part_floats((int)ctc) : 0;
+    p = take(tp); if (w) w->tile_part = tp ? p : nullptr;  // (none: the launches then do not slice)
     return off;
 }
 
@@ -685,8 +692,8 @@ template <int CT, int EPI>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_gemm_tile_q4(const gemm_args a, int bps, float4 *part)
 {
-    constexpr int NW = 8, S = 2, U = 4, TPS = U * CT * 2, NLD = TPS / NW;    // NLD = CT activation tiles per wave and step
-    static_assert(NLD * NW == TPS, "every wave loads the same number of activation tiles");
+    constexpr int NW = 8, S = 2, U = 4, P = U * CT, TPS = P * 2;            // P (K-tile, column tile) pairs = TPS activation tiles per step
+    static_assert(CT == 1 || CT == 2 || CT == 4, "a wave brings in pair `wave` (if there is one) and, with 16 pairs, pair `wave + 8`");
     constexpr bool NORM = (EPI == EPI_QKV || EPI == EPI_SWIGLU || EPI == EPI_LMHEAD);
     extern __shared__ uint4 tile_lds[];                         // [2][TPS][64]
     uint4 (*sa)[TPS][64] = (uint4 (*)[TPS][64])tile_lds;
@@ -712,8 +719,8 @@ k_gemm_tile_q4(const gemm_args a, int bps, float4 *part)
     for (int ct = 0; ct < CT; ++ct) acc0[ct] = acc1[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     struct wslot { uint4 c0, c1; uint2 s0, s1; };               // a batch of either strip
-    static_assert(NLD == 2 || NLD == 4, "activation slots are spelled out");
     struct xslot { uint4 a, b, c, d; };                         // (named members: an array here ends up in scratch memory)
+    const bool loads = wave < P;                                // (CT = 1: four pairs a step, the other four waves bring in none)
     auto batch_of = [&](int step) { int k = min(step, nsteps - 1) + rot; if (k >= nsteps) k -= nsteps; return b0 + k; };   // (a step past the end re-reads the last one)
     auto issue_w = [&](wslot &q, int step) {
         const size_t o = (size_t)batch_of(step) * PV_Q4_BATCH;
@@ -726,17 +733,19 @@ k_gemm_tile_q4(const gemm_args a, int bps, float4 *part)
     auto issue_x = [&](xslot &q, int step) {                    // pair p = wave (+ 8) of the step: K-tile p / CT of the batch, column tile p % CT, hi and lo
         const int bt = batch_of(step);
         auto tile = [&](int p, int half) { const int u = p / CT, ct = p % CT; return B[(size_t)(2 * ct + half) * arr + (size_t)(bt * 4 + u) * 64]; };
-        q.a = tile(wave, 0); q.b = tile(wave, 1);
-        if (NLD == 4) { q.c = tile(wave + NW, 0); q.d = tile(wave + NW, 1); }
+        if (loads) { q.a = tile(wave, 0); q.b = tile(wave, 1); }
+        if (P > NW) { q.c = tile(wave + NW, 0); q.d = tile(wave + NW, 1); }
         asm volatile("" ::: "memory");
     };
     const uint4 neg24 = make_uint4(0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u, 0xC1C0C1C0u);
     auto stage = [&](const xslot &x, int buf) {                 // the wave's tiles of the step into LDS, with -24 x the row sums of each hi + lo pair
         const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
-        sa[buf][2 * wave][lane] = x.a; sa[buf][2 * wave + 1][lane] = x.b;
-        const f32x4 ra = mfma16(x.b, neg24, mfma16(x.a, neg24, zero4));
-        if ((lane & 15) == 0) rs[buf][wave][lane >> 4] = ra;
-        if (NLD == 4) {
+        if (loads) {
+            sa[buf][2 * wave][lane] = x.a; sa[buf][2 * wave + 1][lane] = x.b;
+            const f32x4 ra = mfma16(x.b, neg24, mfma16(x.a, neg24, zero4));
+            if ((lane & 15) == 0) rs[buf][wave][lane >> 4] = ra;
+        }
+        if (P > NW) {
             sa[buf][2 * (wave + NW)][lane] = x.c; sa[buf][2 * (wave + NW) + 1][lane] = x.d;
             const f32x4 rc = mfma16(x.d, neg24, mfma16(x.c, neg24, zero4));
             if ((lane & 15) == 0) rs[buf][wave + NW][lane >> 4] = rc;
@@ -783,7 +792,7 @@ k_gemm_tile_q4(const gemm_args a, int bps, float4 *part)
         for (int r = 0; r < 4; ++r) { acc0[CT - 1][r] = fmaf(ps0, pa[r], acc0[CT - 1][r]); acc1[CT - 1][r] = fmaf(ps1, pb[r], acc1[CT - 1][r]); }
     };
     wslot wA, wB;
-    xslot x;
+    xslot x = {};
     issue_w(wA, 0); issue_w(wB, 1);
     if (NORM && part == nullptr) {                              // (their loads went out before the weights': no wait for those; the
 #pragma unroll                                                  //  registers are free again before the activation slot fills)
@@ -891,7 +900,9 @@ static int allow_tile_q4_lds()
 int pv_mat_gemm_init(void)
 {
     int rc;
-    if ((rc = allow_tile_q4_lds<2, EPI_QKV>()) != PV_OK || (rc = allow_tile_q4_lds<2, EPI_RESID>()) != PV_OK ||
+    if ((rc = allow_tile_q4_lds<1, EPI_QKV>()) != PV_OK || (rc = allow_tile_q4_lds<1, EPI_RESID>()) != PV_OK ||
+        (rc = allow_tile_q4_lds<1, EPI_SWIGLU>()) != PV_OK || (rc = allow_tile_q4_lds<1, EPI_LMHEAD>()) != PV_OK ||
+        (rc = allow_tile_q4_lds<2, EPI_QKV>()) != PV_OK || (rc = allow_tile_q4_lds<2, EPI_RESID>()) != PV_OK ||
         (rc = allow_tile_q4_lds<2, EPI_SWIGLU>()) != PV_OK || (rc = allow_tile_q4_lds<2, EPI_LMHEAD>()) != PV_OK ||
         (rc = allow_tile_q4_lds<4, EPI_QKV>()) != PV_OK || (rc = allow_tile_q4_lds<4, EPI_RESID>()) != PV_OK ||
         (rc = allow_tile_q4_lds<4, EPI_SWIGLU>()) != PV_OK || (rc = allow_tile_q4_lds<4, EPI_LMHEAD>()) != PV_OK) return rc;
@@ -905,10 +916,10 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
     ga.nstrips = strips;
     ga.interleave = g.ktiles > 128;                          // long strips: measured 0.3 % faster per step, short ones 0.3 % slower
     if (m->wbits == 4) {
-        if constexpr (CT == 1) {
+        if constexpr (NB == 1) {
             // Several strips per workgroup share every activation tile from registers (one strip:
             // 4 KiB of tiles from L2 per 1.1 KiB of weights), as many as still leave a workgroup per CU.
-            if constexpr (NB == 1 && (EPI == EPI_QKV || EPI == EPI_SWIGLU)) {
+            if constexpr (EPI == EPI_QKV || EPI == EPI_SWIGLU) {
                 // strips = (k + 1/2) x G with G a multiple of the 256 CUs: G workgroups of k whole strips and
                 // half of a shared one put the same bytes on every CU (see the 16-bit launch below)
                 for (int k = (strips >= 1024 ? 3 : 2); k >= 1 && g.ktiles >= 64; --k) {
@@ -922,18 +933,18 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
                     return PV_OK;
                 }
             }
-            if (NB == 1 && strips >= 1024 && g.ktiles >= 64) k_gemm<1, 1, 4, EPI, 8, 4><<<(strips + 3) / 4, 512, 0, s>>>(ga);
-            else if (NB == 1 && strips >= 512 && g.ktiles >= 64) k_gemm<1, 1, 2, EPI, 8, 4><<<(strips + 1) / 2, 512, 0, s>>>(ga);
-            else if (g.ktiles >= 64) k_gemm<NB, 1, 1, EPI, 16, 4><<<strips, 1024, 0, s>>>(ga);
-            else k_gemm<NB, 1, 1, EPI, 8, 4><<<strips, 512, 0, s>>>(ga);
+            if (strips >= 1024 && g.ktiles >= 64) k_gemm<1, 1, 4, EPI, 8, 4><<<(strips + 3) / 4, 512, 0, s>>>(ga);
+            else if (strips >= 512 && g.ktiles >= 64) k_gemm<1, 1, 2, EPI, 8, 4><<<(strips + 1) / 2, 512, 0, s>>>(ga);
+            else if (g.ktiles >= 64) k_gemm<1, 1, 1, EPI, 16, 4><<<strips, 1024, 0, s>>>(ga);
+            else k_gemm<1, 1, 1, EPI, 8, 4><<<strips, 512, 0, s>>>(ga);
         } else {
-            // 4-bit weights, 17..64 rows: activation tiles shared through LDS, two strips per wave, one workgroup per CU
+            // 4-bit weights, 9..64 rows: activation tiles shared through LDS, two strips per wave, one workgroup per CU
             // (256 registers a lane); few strips: cut along K so that about 256 workgroups run, as for 16-bit weights
             const int nbat = g.ktiles / 4, ngroups = (strips + 15) / 16;
-            int slices = ngroups >= 192 ? 1 : min(TILE_MAX_SLICES, (256 + ngroups - 1) / ngroups);
+            int slices = (ngroups >= 192 || g.tile_part == nullptr) ? 1 : min(TILE_MAX_SLICES, (256 + ngroups - 1) / ngroups);
             int bps = max(4, (nbat + slices - 1) / slices);
             slices = (nbat + bps - 1) / bps;
-            while (slices > 1 && (size_t)slices * strips * CT * 256 > TILE_PART_FLOATS) { bps += 1; slices = (nbat + bps - 1) / bps; }
+            while (slices > 1 && (size_t)slices * strips * CT * 256 > tile_part_floats(CT)) { bps += 1; slices = (nbat + bps - 1) / bps; }
             float4 *part = slices > 1 ? (float4 *)g.tile_part : nullptr;
             k_gemm_tile_q4<CT, EPI><<<dim3(ngroups, slices), 512, tile_q4_lds(CT), s>>>(ga, bps, part);
             PV_HIP(hipGetLastError());
@@ -949,11 +960,11 @@ static int launch_gemm(const pv_model *m, const gemm_args &g, int strips, hipStr
             // activation tiles shared through LDS; few strips: cut along K so that about 256 workgroups run
             if (g.ktiles >= 16) {
                 const int ngroups = (strips + 7) / 8;
-                int slices = ngroups >= 192 ? 1 : min(TILE_MAX_SLICES, (256 + ngroups - 1) / ngroups);
+                int slices = (ngroups >= 192 || g.tile_part == nullptr) ? 1 : min(TILE_MAX_SLICES, (256 + ngroups - 1) / ngroups);
                 int tps = (g.ktiles + slices - 1) / slices;
                 tps = max(8, (tps + 1) & ~1);                        // whole steps, at least four per slice
                 slices = (g.ktiles + tps - 1) / tps;
-                while (slices > 1 && (size_t)slices * strips * CT * 256 > TILE_PART_FLOATS) { tps += 2; slices = (g.ktiles + tps - 1) / tps; }
+                while (slices > 1 && (size_t)slices * strips * CT * 256 > tile_part_floats(CT)) { tps += 2; slices = (g.ktiles + tps - 1) / tps; }
                 float4 *part = slices > 1 ? (float4 *)g.tile_part : nullptr;
                 k_gemm_tile<CT, 1, EPI><<<dim3(ngroups, slices), 512, 0, s>>>(ga, tps, part);
                 PV_HIP(hipGetLastError());

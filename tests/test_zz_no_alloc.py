@@ -16,6 +16,7 @@ pytestmark = pytest.mark.gpu
 
 MAT = pv_inputs.ModelShape("na_mat", 3, 256, 8, 2, 64, 704, 1024, rope_base=500000.0, dtype="bf16", seed=6101)
 SLIM = pv_inputs.ModelShape("na_slim", 1, 128, 4, 2, 32, 128, 512, dtype="bf16", seed=6102)
+MAT_Q4 = pv_inputs.ModelShape("na_q4", 2, 512, 8, 2, 64, 1408, 1008, rope_base=500000.0, dtype="bf16", seed=6103, weight_bits=4)
 
 
 @pytest.fixture(scope="module")
@@ -71,6 +72,10 @@ def test_static_scratch_step_equals_workspace_step(pvlib):
     _twin_steps(pvlib, m, MAT, (16, 5, 1))
     # the vector path too, against its own workspace step
     _twin_steps(pvlib, tiny, CONFIGS["tiny"], (4, 2))
+    # 4-bit weights: 9..16-row blocks run the K-sliced shared-tile GEMM, whose partial sums sit in the step's buffers
+    # (here: in the fixed array, laid out for 16 rows)
+    q4 = gpu_model(MAT_Q4, gains="perturbed")
+    _twin_steps(pvlib, q4, MAT_Q4, (12, 16, 7))
 
 
 def test_static_scratch_refuses_what_does_not_fit(pvlib):
