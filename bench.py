@@ -17,7 +17,7 @@ read-only stream of the step's byte count reaches on this device in this run; `c
 the CPU oracle timed on a bounded slice of the same workload.  With no --workload / --gamma
 given, `also` carries the other points of the metric measured the same way in the same run:
 the 8B shape at gamma 1, 4, 16, batched verification of 4 sequences x gamma 8 on the 8B shape, and the
-70B-shaped verifier (prefix 1024, gamma 8).
+70B-shaped verifier (prefix 1024, gamma 8) with 16-bit and with 4-bit weights.
 """
 import argparse
 import gc
@@ -308,7 +308,7 @@ def main():
     ap.add_argument("--prefix", type=int, default=None)
     ap.add_argument("--alpha", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-also", action="store_true", help="headline workload only (no gamma sweep, no 70B-shaped run)")
+    ap.add_argument("--no-also", action="store_true", help="headline workload only (no gamma sweep, no 70B-shaped runs)")
     ap.add_argument("--batch", type=int, default=None, metavar="B",
                     help="also time batched verification of B sequences x gamma drafts (default run: 4)")
     ap.add_argument("--no-graphs", action="store_true", help="plain launches instead of HIP-graph replay of the step (comparison runs)")
@@ -363,15 +363,16 @@ def main():
         del src, dst
     wl.close()
 
-    if sweep:                                   # the other shape the metric is quoted on
-        T70, g70, a70 = DEFAULTS["70b"]
-        w70 = Workload(pv, pv_inputs, "70b", T70, [g70], K + W, use_graphs=not a.no_graphs)
-        r70 = w70.run(g70, a70, K, W, prof_kernel=a.prof_kernel)
-        with_ceiling(r70, w70.stream_ceiling(r70["step_bytes"], r70["roofline"]["bytes_per_launch"]))
-        r70["workload"] = f"70b-shaped verifier, prefix {T70}, gamma {g70}, alpha {a70}, batch 1"
-        also[f"70b_gamma{g70}"] = r70
-        log(f"70b gamma {g70}: {r70['ms_per_step']:.3f} ms/step")
-        w70.close()
+    if sweep:                                   # the other shape the metric is quoted on, with 16-bit weights and in 4 bit (Sec. 4.1)
+        for other in ("70b", "70b_q4"):
+            T70, g70, a70 = DEFAULTS[other]
+            w70 = Workload(pv, pv_inputs, other, T70, [g70], K + W, use_graphs=not a.no_graphs)
+            r70 = w70.run(g70, a70, K, W, prof_kernel=a.prof_kernel)
+            with_ceiling(r70, w70.stream_ceiling(r70["step_bytes"], r70["roofline"]["bytes_per_launch"]))
+            r70["workload"] = f"{other}-shaped verifier, prefix {T70}, gamma {g70}, alpha {a70}, batch 1"
+            also[f"{other}_gamma{g70}"] = r70
+            log(f"{other} gamma {g70}: {r70['ms_per_step']:.3f} ms/step")
+            w70.close()
 
     out = {
         "metric": "verify_tokens_per_s", "value": head["verified_tokens_per_s"], "unit": "tok/s",
