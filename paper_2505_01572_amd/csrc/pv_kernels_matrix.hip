@@ -7,8 +7,8 @@
 // owns one or a few strips, its wavefronts split K, accumulate in fp32, and are summed in wave
 // order through LDS, so the owner sees complete outputs and the whole epilogue (RMSNorm scale,
 // rotary embedding + KV append, SwiGLU, residual add, vocabulary arg-max) is fused into the
-// GEMM.  17..64 rows (k_gemm_tile): the waves of a workgroup own different strips, walk K
-// together and share the activation tiles through LDS.
+// GEMM.  17..64 rows (k_gemm_tile; with 4-bit weights k_gemm_tile_q4, from 9 rows on): the waves
+// of a workgroup own different strips, walk K together and share the activation tiles through LDS.
 //
 // Activations enter as the B operand.  To keep fp32-grade accuracy with bf16 matrix cores an
 // activation a is carried as two bf16 numbers hi = bf16(a), lo = bf16(a - hi) (16 mantissa
@@ -676,7 +676,7 @@ k_gemm_tile(const gemm_args a, int tps, float4 *part)
 }
 
 // ------------------------------------------------------------------------------------------
-// The same for 4-bit weights (17..64 rows): the 8 waves of a workgroup own two strips each and walk
+// The same for 4-bit weights (9..64 rows, CT = 1, 2 or 4): the 8 waves of a workgroup own two strips each and walk
 // the strips' batches (4 K-tiles of codes + scales, 1152 bytes) in step; the 8 CT activation tiles of
 // a step are fetched once per workgroup and shared through LDS (two buffers, one barrier per step).
 // Per weight byte a 4-bit strip needs 3.6 times the activation bytes of a 16-bit one, on the L2 -> CU
