@@ -84,8 +84,7 @@ typedef struct {
                            * the LM head are 4-bit codes with one bf16 scale per 32 input
                            * features, weight = (code - 8) * scale (the 4-bit target model of the
                            * paper's Sec. 4.1; format chosen by this library); needs PV_BF16, the
-                           * matrix path, input widths that are multiples of 128; blocks of more than
-                           * 16 rows take one pass over the weights per 16 rows */
+                           * matrix path, input widths that are multiples of 128 */
 } pv_model_config;
 
 #define PV_Q4_GROUP 32      /* input features per scale of a 4-bit matrix */
@@ -151,7 +150,7 @@ int pv_cache_set_page_table(pv_cache *c, const int32_t *phys_pages, int32_t n_pa
 /*
  * The prefill phase of Sec. 2.1 (the prompt is processed in parallel before decoding starts):
  * append n prompt tokens (host array), all accepted, in chunks of at most max_gamma rows
- * (matrix path with 16-bit weights: of up to 64 rows, whatever max_gamma is).
+ * (matrix path: of up to 64 rows, whatever max_gamma is).
  * Afterwards length += n and pending = the stage's greedy token after the prompt.
  * Synchronises hip_stream before returning.
  */
