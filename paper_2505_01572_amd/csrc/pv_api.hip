@@ -513,6 +513,17 @@ extern "C" int pv_calib_copy(void *d_dst, const void *d_src, size_t nbytes, void
 // after the step's stream has been synchronised: fold the step's results into the host mirror
 // every wave streams a contiguous slice of `tiles` 1 KiB tiles (64 lanes x 16 bytes), eight loads in
 // flight per lane; the rest of the region is read by the first waves, one tile each
+typedef __attribute__((ext_vector_type(4))) unsigned int calib_u32x4;
+__device__ inline uint4 calib_load(const uint4 *p)
+{
+#ifdef PV_CALIB_PLAIN
+    return *p;
+#else
+    const calib_u32x4 v = __builtin_nontemporal_load((const calib_u32x4 *)p);   // read once, like the weight streams it is compared with
+    return make_uint4(v.x, v.y, v.z, v.w);
+#endif
+}
+
 __global__ void __launch_bounds__(512) k_calib_read(const uint4 *__restrict__ src, size_t tiles, size_t n, uint4 *sink)
 {
     const int lane = threadIdx.x & 63;
@@ -522,7 +533,7 @@ __global__ void __launch_bounds__(512) k_calib_read(const uint4 *__restrict__ sr
     for (size_t t = 0; t < tiles; t += 8) {
         uint4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = q[(t + u) * 64];
+        for (int u = 0; u < 8; ++u) v[u] = calib_load(&q[(t + u) * 64]);
 #pragma unroll
         for (int u = 0; u < 8; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
     }

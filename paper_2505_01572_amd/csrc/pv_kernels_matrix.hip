@@ -335,8 +335,8 @@ k_gemm(const gemm_args a)
             for (int si = 0; si < S; ++si) {
                 const char *p = Aq + qo[si] + (size_t)bt * PV_Q4_BATCH;
                 const int ln = lane + ((HF && si == S - 1) ? hl : 0);
-                q.c[si] = *(const uint4 *)(p + ln * 16);
-                q.s[si] = *(const uint2 *)(p + 1024 + (ln & 15) * 8);
+                q.c[si] = load_once((const uint4 *)(p + ln * 16));
+                q.s[si] = load_once((const uint2 *)(p + 1024 + (ln & 15) * 8));
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -406,7 +406,7 @@ k_gemm(const gemm_args a)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int si = 0; si < S; ++si) q.w[si][u] = A[so[si] + o + u * 64 + ((HF && si == S - 1) ? hl : 0)];
+                for (int si = 0; si < S; ++si) q.w[si][u] = load_once(&A[so[si] + o + u * 64 + ((HF && si == S - 1) ? hl : 0)]);
                 q.x[u] = B[o + u * 64];
                 if (NB == 2) q.xl[NB == 2 ? u : 0] = B[arr + o + u * 64];
             }
@@ -440,7 +440,7 @@ k_gemm(const gemm_args a)
                 if (NB == 2) xl = B[arr + (size_t)t * 64];
 #pragma unroll
                 for (int si = 0; si < S; ++si) {
-                    const uint4 w = A[so[si] + (size_t)t * 64 + ((HF && si == S - 1) ? hl : 0)];
+                    const uint4 w = load_once(&A[so[si] + (size_t)t * 64 + ((HF && si == S - 1) ? hl : 0)]);
                     acc[si][0] = mfma16(w, x, acc[si][0]);
                     if (NB == 2) acc[si][0] = mfma16(w, xl, acc[si][0]);
                 }
@@ -453,7 +453,7 @@ k_gemm(const gemm_args a)
         for (int u = 0; u < U; ++u) {
             const size_t o = (size_t)(t + u) * 64;
 #pragma unroll
-            for (int si = 0; si < S; ++si) ra[si][u] = A[so[si] + o];
+            for (int si = 0; si < S; ++si) ra[si][u] = load_once(&A[so[si] + o]);
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 rb[ct][u] = B[(size_t)(2 * ct) * arr + o];
@@ -506,7 +506,7 @@ k_gemm(const gemm_args a)
                 if (NB == 2) bl = B[(size_t)(2 * ct + 1) * arr + o];
 #pragma unroll
                 for (int si = 0; si < S; ++si) {
-                    const uint4 wa = A[so[si] + o];
+                    const uint4 wa = load_once(&A[so[si] + o]);
                     acc[si][ct] = mfma16(wa, bh, acc[si][ct]);
                     if (NB == 2) acc[si][ct] = mfma16(wa, bl, acc[si][ct]);
                 }
@@ -600,7 +600,7 @@ k_gemm_tile(const gemm_args a, int tps, float4 *part)
 #pragma unroll
         for (int si = 0; si < S; ++si)
 #pragma unroll
-            for (int u = 0; u < U; ++u) q.w[si][u] = A[so[si] + (size_t)min(tb + u, t1 - 1) * 64];
+            for (int u = 0; u < U; ++u) q.w[si][u] = load_once(&A[so[si] + (size_t)min(tb + u, t1 - 1) * 64]);
         asm volatile("" ::: "memory");
     };
     auto use = [&](const slot &q, int buf, int step) {   // q holds step `step`: share its activation tiles through sa[buf], multiply
@@ -724,10 +724,10 @@ k_gemm_tile_q4(const gemm_args a, int bps, float4 *part)
     auto batch_of = [&](int step) { int k = min(step, nsteps - 1) + rot; if (k >= nsteps) k -= nsteps; return b0 + k; };   // (a step past the end re-reads the last one)
     auto issue_w = [&](wslot &q, int step) {
         const size_t o = (size_t)batch_of(step) * PV_Q4_BATCH;
-        q.c0 = *(const uint4 *)(Aq0 + o + lane * 16);
-        q.c1 = *(const uint4 *)(Aq1 + o + lane * 16);
-        q.s0 = *(const uint2 *)(Aq0 + o + 1024 + (lane & 15) * 8);
-        q.s1 = *(const uint2 *)(Aq1 + o + 1024 + (lane & 15) * 8);
+        q.c0 = load_once((const uint4 *)(Aq0 + o + lane * 16));
+        q.c1 = load_once((const uint4 *)(Aq1 + o + lane * 16));
+        q.s0 = load_once((const uint2 *)(Aq0 + o + 1024 + (lane & 15) * 8));
+        q.s1 = load_once((const uint2 *)(Aq1 + o + 1024 + (lane & 15) * 8));
         asm volatile("" ::: "memory");
     };
     auto issue_x = [&](xslot &q, int step) {                    // pair p = wave (+ 8) of the step: K-tile p / CT of the batch, column tile p % CT, hi and lo
