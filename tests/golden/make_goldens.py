@@ -18,13 +18,14 @@ Stored per step: start position, pending token, draft, per-row argmax, top-2 mar
 row's logits, accepted length, correction token, the row's logits at a fixed strided set of ids and at
 its 64 largest ids; plus K/V of sampled (layer, position) pairs after the prompt.
 
-    python tests/golden/make_goldens.py 8b            # one of: 1b 7b 8b 70b 70b_v128k  (or a test shape)
+    python tests/golden/make_goldens.py 8b            # one of: 1b 7b 8b 70b 70b_v128k 70b_q4  (or a test shape)
 """
 import argparse
 import json
 import os
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
@@ -43,6 +44,7 @@ PLANS = {
     "8b": ("chain", 2048, (0.7,), (8, 16, 4, 1, 8, 8), 0),
     "70b": ("tree", 1024, (0.6,), (8, 8, 8, 8, 16, 1), 5),
     "70b_v128k": ("tree", 256, (0.6,), (8, 8, 8, 1), 4),
+    "70b_q4": ("tree", 128, (0.6,), (8, 8, 1), 2),            # the 70B shape in 4 bit (Sec. 4.1); prompt cut to 128 (CPU time)
 }
 TOP = 64
 
@@ -108,6 +110,14 @@ def tensor_source(shape, keep):
         if (kind, layer) in held:
             return held[(kind, layer)]
         a = pv_inputs.fill_tensor(shape, kind, layer).reshape(pv_inputs.tensor_shape(shape, kind))
+        if getattr(shape, "weight_bits", 16) == 4 and kind in pv_inputs.Q4_KINDS:
+            # the model's weights ARE the codes and scales; the oracle runs on their float32 values (exact).
+            # Rows are independent: the oracle's routine is called on row blocks from a few threads.
+            codes, scales = pv_inputs.quantize_q4(a)
+            cuts = list(range(0, a.shape[0], 2048)) + [a.shape[0]]
+            with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+                parts = list(pool.map(lambda i: ref.dequant_q4(codes[cuts[i]:cuts[i + 1]], scales[cuts[i]:cuts[i + 1]]), range(len(cuts) - 1)))
+            a = np.concatenate(parts) if len(parts) > 1 else parts[0]
         if keep:
             held[(kind, layer)] = a
         return a

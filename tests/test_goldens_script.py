@@ -5,6 +5,7 @@ import json
 import os
 
 import numpy as np
+import pytest
 
 import pv_inputs
 from oracle import ref, replay
@@ -39,12 +40,16 @@ def test_layerwise_drive_equals_block_forward_bit_for_bit():
     assert np.array_equal(run.run([(53, b2)])[0], c.forward_block(b2))
 
 
-def test_golden_script_records_what_the_plain_oracle_computes(tmp_path):
+GQA_Q4 = pv_inputs.ModelShape("gqa_small_q4", 3, 128, 8, 2, 32, 192, 512, rope_base=500000.0, dtype="bf16", seed=4343, weight_bits=4)
+
+
+@pytest.mark.parametrize("GQA", [GQA, GQA_Q4], ids=["bf16", "q4"])
+def test_golden_script_records_what_the_plain_oracle_computes(tmp_path, GQA):
     mg = _script()
     out_c, out_t = str(tmp_path / "chain.npz"), str(tmp_path / "tree.npz")
     mg.make("x", GQA, ("chain", 100, (0.5, 0.8), (8, 16, 1, 4), 0), out_c)
     mg.make("x", GQA, ("tree", 100, (0.6,), (8, 8, 16, 1), 3), out_t)
-    rm = ref_model(GQA)
+    rm = ref_model(GQA)                                      # (4-bit shapes: the dequantised codes, by the plain route)
     prompt = pv_inputs.uniform_tokens(2000 + GQA.seed, 100, GQA.vocab)
     for path in (out_c, out_t):
         g = np.load(path)

@@ -1,7 +1,8 @@
 """Every benchmark configuration at full depth against the CPU oracle.
 
 tests/golden/verify_<config>.npz hold what the oracle (fp64, K/V rounded to bf16 on store) computes
-for the 1B-, 7B-, 8B- and 70B-shaped verifiers with all their layers on their benchmark prompts:
+for the 1B-, 7B-, 8B- and 70B-shaped verifiers (the 70B shape also with the 128k vocabulary and, on a
+prompt of 128 tokens, with 4-bit weights) with all their layers on their benchmark prompts:
 written by tests/golden/make_goldens.py, which calls only oracle/ and pv_inputs/.  Here the library
 is loaded with the same seeded weights, prefills the same prompt and takes the same verify steps
 through the C ABI, in the launch configuration bench.py times (graph replay, 16-row model).
@@ -72,7 +73,7 @@ def _bring_to(c, T0, T, pending, G):
     assert c.state() == (T, pending)
 
 
-@pytest.mark.parametrize("name", ["1b", "7b", "8b", "70b", "70b_v128k"])
+@pytest.mark.parametrize("name", ["1b", "7b", "8b", "70b", "70b_v128k", "70b_q4"])
 def test_full_depth_steps_match_oracle_goldens(pvlib, name):
     import bench
     g = np.load(os.path.join(GOLDEN, f"verify_{name}.npz"))
