@@ -268,7 +268,7 @@ __device__ inline void k_walk(int cnt, Q &q0, Q &q1, Q &q2, FI issue, FC consume
 // features) so that a lane's four results share one feature, hence one scale; the accumulators
 // are turned back on their way through the LDS reduction.
 template <int NB, int CT, int S, int EPI, int NW, int WB = 16, int DP = 1, bool HF = false>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((NB == 1 && S == 1 && WB == 16 && DP == 1) ? 8 : 4)))   // packed bf16 rows, one strip: <= 64 VGPRs, two 16-wave workgroups per CU
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((NB == 1 && S == 1 && WB == 16 && DP == 1) ? 8 : (S * CT >= 16) ? 2 : 4)))   // packed bf16 rows, one strip: <= 64 VGPRs, two 16-wave workgroups per CU; 16 accumulator tiles (wide blocks with a short K): more than 128
 k_gemm(const gemm_args a)
 {
     static_assert(NB == 2 || CT == 1, "packed rows come in one tile");
