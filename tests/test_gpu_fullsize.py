@@ -104,6 +104,46 @@ def test_full_width_wide_blocks_two_layers(pvlib, name, T0):
     _compare_steps(pvlib, gm, rm, shape, T0, (64, 17, 32, 8, 40), 0.7, 7200)
 
 
+@pytest.mark.parametrize("name,T0", [("8b", 300), ("70b_q4", 130)])
+def test_full_width_draft_tree_two_layers(pvlib, name, T0):
+    """A draft tree of 48 nodes at full width (head_dim 128, four / eight query heads per kv head): every probed node's
+    logits are the oracle's block forward over its chain of ancestors, the accepted path is the oracle's greedy
+    continuation as far as the tree carries it, and the compacted cache equals the oracle's after the same tokens."""
+    from gpu_helpers import paired_models, logit_scale, top2_margin
+    from helpers import greedy_continuation
+    from test_gpu_tree import _tree, _chain
+    shape = CONFIGS[name].replace(n_layers=2)
+    gm, rm = paired_models(shape, max_gamma=64)
+    prompt = pv_inputs.uniform_tokens(2000 + shape.seed, T0, shape.vocab)
+    gc, rc, ar = pvlib.Cache(gm, T0 + 160), ref.RefCache(rm, T0 + 160, ref.KV_BF16), ref.RefCache(rm, T0 + 160, ref.KV_BF16)
+    gc.prefill(prompt); rc.prefill(prompt); ar.prefill(prompt)
+    assert gc.state() == (T0, rc.pending)
+    G = greedy_continuation(ar, 10)
+    tokens, parents, want_path = _tree(G, 48, 7300, shape.vocab, 6)
+    n_g, nxt_g, path_g = gc.verify_tree(T0, tokens, parents)
+    lg_g = gc.debug_logits()
+    probe = sorted(set(want_path[-1:] + [47, 24, 0] + [i for i in range(48) if i not in set(parents)][:3]))
+    worst = 0.0
+    for i in probe:
+        ch = _chain(parents, i)
+        lg_r = rc.forward_block(tokens[ch]); rc.rollback(T0)
+        worst = max(worst, float((np.abs(lg_g[ch] - lg_r) / logit_scale(lg_r)).max()))
+    assert worst < 5e-3, worst
+    m = len(want_path)
+    lg_path = rc.forward_block(tokens[want_path]); rc.rollback(T0)
+    if (top2_margin(lg_path) > 0.05).all():
+        assert (n_g, list(path_g)) == (m, want_path) and nxt_g == G[m]
+        assert gc.state() == (T0 + m, int(G[m]))
+    rc.pending = int(G[0])
+    if n_g:
+        rc.verify(T0, tokens[list(path_g)])
+    assert len(rc) == len(gc)
+    ge, re_ = pv_inputs.bf16_bits_to_f32(gc.export()).astype(np.float64), rc.export()
+    flips = (ge != re_).mean(axis=(1, 2, 3))
+    assert flips[0] < FLIP_BOUND_L0 and flips.max() < FLIP_BOUND and np.abs(ge - re_).max() <= 2.0 ** -7 * np.abs(re_).max()
+    print(f"[{name}] tree of 48 nodes: accepted {n_g} (path {[int(i) for i in path_g]}), worst relative logit error {worst:.2e}, K/V flips per layer {flips}", flush=True)
+
+
 @pytest.mark.parametrize("name,T0", [("8b", 96), ("7b", 96)])
 def test_full_depth_short_prefix(pvlib, name, T0):
     """Every layer at full width; the prompt is cut to what the oracle prefills in seconds."""
