@@ -72,10 +72,12 @@ def load_model(pv, pv_inputs, shape, max_gamma, kernel_path=0):
     return m
 
 
-def cpu_baseline(pv_inputs, shape, gamma, budget_s=20.0):
-    """Oracle timed on the host: gamma-row verify steps on 1- and 2-layer slices of the shape
-    (prefix 64), repeated until about budget_s seconds of oracle work have been timed, the
-    per-step medians extrapolated linearly in the layer count to the full depth."""
+def cpu_baseline(pv_inputs, shape, gamma, prefix, budget_s=20.0):
+    """Oracle timed on the host: gamma-row verify steps on 1- and 2-layer slices of the shape at the
+    workload's prefix length (the slices' caches are set to that length without running the prompt:
+    the keys and values are the zeros they were allocated with, which costs the oracle the same
+    arithmetic), repeated until about budget_s seconds of oracle work have been timed, the per-step
+    medians extrapolated linearly in the layer count to the full depth."""
     import numpy as np
     from oracle import ref
     from helpers import ref_model
@@ -84,16 +86,15 @@ def cpu_baseline(pv_inputs, shape, gamma, budget_s=20.0):
     for nl in (1, 2):
         s = shape.replace(n_layers=nl)
         rm = ref_model(s)
-        c = ref.RefCache(rm, 64 + 4 * gamma, ref.KV_BF16 if s.dtype == "bf16" else ref.KV_REAL)
-        c.forward_block(pv_inputs.uniform_tokens(2000, 64, s.vocab), want_logits=False)
-        c.pending = -1
+        c = ref.RefCache(rm, prefix + 4 * gamma, ref.KV_BF16 if s.dtype == "bf16" else ref.KV_REAL)
+        c.set_len(prefix)
         dts, t_used = [], 0.0
         while len(dts) < 3 or (t_used < budget_s / 2 and len(dts) < 400):
             d = pv_inputs.uniform_tokens(2100 + len(dts), gamma, s.vocab)
             t0 = time.time()
             c.verify(len(c), d)
             dt = time.time() - t0
-            c.rollback(64)
+            c.rollback(prefix)
             dts.append(dt); t_used += dt
         times[nl], reps[nl] = float(np.median(dts)), len(dts)
         del c, rm
@@ -102,8 +103,8 @@ def cpu_baseline(pv_inputs, shape, gamma, budget_s=20.0):
     full = head + per_layer * shape.n_layers
     return {"value": gamma / full, "unit": "tok/s", "cores": cores, "kind": "oracle", "real": "f64",
             "sample": f"gamma={gamma} verify steps of the oracle as the parity tests use it (fp64 build) on 1- and 2-layer slices of "
-                      f"the {shape.name} shape (prefix 64, not the workload's: the oracle's attention over the full prefix, a few "
-                      f"percent of its step, is left out; {reps[1]} and {reps[2]} steps, about {budget_s:.0f} s of timed work; medians): "
+                      f"the {shape.name} shape at the workload's prefix of {prefix} (cache length set, prompt not run: the prefix's keys and "
+                      f"values are zeros; {reps[1]} and {reps[2]} steps, about {budget_s:.0f} s of timed work; medians): "
                       f"{per_layer:.3f} s/layer + {head:.3f} s for embedding, final norm and LM head, "
                       f"extrapolated to {shape.n_layers} layers = {full:.2f} s/step"}
 
@@ -389,7 +390,7 @@ def main():
         out["also"] = also
     if not a.no_cpu_baseline:
         t0 = time.time()
-        out["cpu_baseline"] = cpu_baseline(pv_inputs, shape, gamma)
+        out["cpu_baseline"] = cpu_baseline(pv_inputs, shape, gamma, T0)
         log(f"cpu baseline: {time.time() - t0:.1f}s")
     print(json.dumps(out), flush=True)
 
