@@ -13,7 +13,8 @@ Prints ONE JSON line.  The top-level fields describe the headline workload (8B-s
 prefix 2048, gamma 8): `value` = verified draft positions per second (gamma * steps / s);
 `roofline` = the dominant kernel (the gate/up projection stream), timed with HIP events on the
 step's stream in a second, instrumented pass over the same steps; `stream_ceiling` = what a plain
-read-only stream of the step's byte count reaches on this device in this run; `cpu_baseline` =
+read-only stream of the step's byte count reaches on this device in this run; `prefill_tokens_per_s` =
+the prompt's rate when it was fed in (once, 64-row chunks, outside the timed region); `cpu_baseline` =
 the CPU oracle timed on a bounded slice of the same workload.  With no --workload / --gamma
 given, `also` carries the other points of the metric measured the same way in the same run:
 the 8B shape at gamma 1, 4, 16, batched verification of 4 sequences x gamma 8 on the 8B shape, and the
@@ -135,8 +136,9 @@ class Workload:
         if not use_graphs:
             self.cache.use_graphs(False)
         t0 = time.time()
-        self.cache.prefill(pv_inputs.uniform_tokens(2000 + shape.seed, T0, shape.vocab))
-        log(f"{name}: prefill of {T0} tokens: {time.time() - t0:.2f}s")
+        self.cache.prefill(pv_inputs.uniform_tokens(2000 + shape.seed, T0, shape.vocab))     # (synchronises)
+        self.prefill_s = time.time() - t0
+        log(f"{name}: prefill of {T0} tokens: {self.prefill_s:.2f}s")
         # the verifier's own greedy continuation (gamma=1 steps), then back to the prompt
         self.first = self.cache.pending
         need = n_steps * gmax + gmax + 1
@@ -184,7 +186,8 @@ class Workload:
         r = {"gamma": gamma, "prefix": self.T0, "alpha": alpha, "ms_per_step": elapsed / K * 1e3, "steps_per_s": K / elapsed,
              "verified_tokens_per_s": gamma * K / elapsed, "committed_tokens_per_s": accepted / elapsed,
              "mean_accepted_len": accepted / K, "step_bytes": step_bytes,
-             "step_hbm_gbps": step_bytes / (elapsed / K) / 1e9, "step_hbm_frac": step_bytes / (elapsed / K) / 1e9 / HBM_PEAK_GBPS}
+             "step_hbm_gbps": step_bytes / (elapsed / K) / 1e9, "step_hbm_frac": step_bytes / (elapsed / K) / 1e9 / HBM_PEAK_GBPS,
+             "prefill_tokens_per_s": self.T0 / self.prefill_s}     # the prompt, once, in 64-row chunks (untimed region; wall clock with its launch)
         if prof_kernel:
             c.rollback(T)
             c.set_pending(int(self.G[T - self.T0]))
@@ -384,6 +387,7 @@ def main():
         "steps_per_s": head["steps_per_s"], "committed_tokens_per_s": head["committed_tokens_per_s"],
         "mean_accepted_len": head["mean_accepted_len"],
         "step_bytes": head["step_bytes"], "step_hbm_gbps": head["step_hbm_gbps"], "step_hbm_frac": head["step_hbm_frac"],
+        "prefill_tokens_per_s": head["prefill_tokens_per_s"],
         "stream_ceiling": head["stream_ceiling"], "roofline": head["roofline"],
     }
     if also:
