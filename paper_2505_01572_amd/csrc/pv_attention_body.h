@@ -42,6 +42,7 @@ struct attn_args {
     float *part_ml;             // [n_kv_heads][MP][max_chunks][32][2]  (max, sum)
     uint16_t *xop_o;            // merge output: operand of the output projection, K = n_q_heads*hd
     int n_pages;                // entries of the page table
+    int lo_off;                 // column offset of the lo halves in the output operand's tiles (packed rows)
 };
 
 __device__ inline void split8(const float v[8], uint4 &hi, uint4 &lo)
@@ -287,6 +288,6 @@ __device__ inline void attn_merge_unit(const attn_args &a, int r, int aq, int n_
     }
     const float inv = 1.0f / L;
     const float y[4] = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
-    store_operand4<NB>(a.xop_o, a.n_q_heads * HD, r, aq * HD + 4 * t, y);
+    store_operand4<NB>(a.xop_o, a.n_q_heads * HD, r, aq * HD + 4 * t, y, a.lo_off);
 }
 

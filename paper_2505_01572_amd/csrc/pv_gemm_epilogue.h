@@ -16,6 +16,7 @@ struct gemm_args {
     float *tile_part;           // scratch for the K-slice partial sums of k_gemm_tile
     int nstrips;                // strips of this GEMM (a workgroup may own several; the last one may be ragged)
     const pv_dev_state *st;
+    int lo_off;                 // packed rows (NB == 1): column offset of the lo halves in operand tiles, 8, or 4 for blocks of at most 4 rows
     // RMSNorm scale of the input rows (QKV, SWIGLU, LMHEAD)
     const float *ssq; int ssq_parts; float inv_d, eps;
     // QKV
@@ -35,7 +36,7 @@ struct gemm_args {
 // squares are kept per tile as [ct][d/16 strips][16].
 template <int NB>
 __device__ inline void emit_x(int lane, int rows, int strip, int d, const float v[4], uint2 gain4,
-                              float *x, float *ssq, uint16_t *xop, int ct = 0)
+                              float *x, float *ssq, uint16_t *xop, int ct, int lo_off)
 {
     const int jl = lane & 15, j = ct * 16 + jl, g = lane >> 4, n = strip * 16 + 4 * g;
     const bool live = j < rows;
@@ -47,7 +48,7 @@ __device__ inline void emit_x(int lane, int rows, int strip, int d, const float 
     if (live) {
         const float y[4] = {v[0] * pv_bf16_to_f32((uint16_t)(gain4.x & 0xffffu)), v[1] * pv_bf16_to_f32((uint16_t)(gain4.x >> 16)),
                             v[2] * pv_bf16_to_f32((uint16_t)(gain4.y & 0xffffu)), v[3] * pv_bf16_to_f32((uint16_t)(gain4.y >> 16))};
-        store_operand4<NB>(xop, d, j, n, y);
+        store_operand4<NB>(xop, d, j, n, y, lo_off);
     }
 }
 
@@ -171,7 +172,7 @@ __device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 
     const int j = ct * 16 + (lane & 15), g = lane >> 4, rows = p.rows;
     float v[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) v[r] = (NB == 1) ? sum[r] + __shfl_down(sum[r], 8, 64) : sum[r];
+    for (int r = 0; r < 4; ++r) v[r] = (NB == 1) ? sum[r] + __shfl_down(sum[r], 8, 64) : sum[r];   // hi + lo columns (lo_off == 4: the loads put the lo columns into 8..11 as well)
     const bool live = j < rows;          // NB == 1 implies rows <= 8, so live lanes hold the combined value
     if (NORM) {
 #pragma unroll
@@ -220,7 +221,7 @@ __device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 
         }
     } else if (EPI == EPI_RESID) {
         v[0] += p.xo.x; v[1] += p.xo.y; v[2] += p.xo.z; v[3] += p.xo.w;       // xo is zero on dead lanes
-        emit_x<NB>(lane, rows, strip, a.d, v, p.gn, a.x, a.ssq_out, a.xop_out, ct);
+        emit_x<NB>(lane, rows, strip, a.d, v, p.gn, a.x, a.ssq_out, a.xop_out, ct, a.lo_off);
     } else if (EPI == EPI_SWIGLU) {
         float act[4];
 #pragma unroll
@@ -228,7 +229,7 @@ __device__ inline void epi_apply(const gemm_args &a, int strip, int lane, f32x4 
             const float up = __shfl_xor(v[r], 16, 64);
             act[r] = v[r] / (1.0f + expf(-v[r])) * up;
         }
-        if (live && !(g & 1)) store_operand4<NB>(a.xop_act, a.F, j, strip * 8 + 4 * (g >> 1), act);
+        if (live && !(g & 1)) store_operand4<NB>(a.xop_act, a.F, j, strip * 8 + 4 * (g >> 1), act, a.lo_off);
     } else {   // EPI_LMHEAD
         const int n = strip * 16 + 4 * g;
         if (live) *(float4 *)(a.logits + (size_t)j * a.vocab + n) = make_float4(v[0], v[1], v[2], v[3]);

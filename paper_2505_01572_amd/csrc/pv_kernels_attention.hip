@@ -92,7 +92,7 @@ int pv_mat_attention(pv_cache *c, int layer, int rows, float *part, uint16_t *xo
     a.scale = 1.0f / sqrtf((float)f.head_dim);
     a.part_o = part;
     a.part_ml = part + (size_t)f.n_kv_heads * c->units_cap * a.max_chunks * 32 * f.head_dim;
-    a.xop_o = xop_o; a.n_pages = c->n_pages;
+    a.xop_o = xop_o; a.n_pages = c->n_pages; a.lo_off = pv_lo_off(rows);
     const bool nb1 = rows <= 8;
     switch (f.head_dim) {
     case 32: return nb1 ? launch<1, 32>(c, a, rows, s) : launch<2, 32>(c, a, rows, s);

@@ -13,7 +13,8 @@
 // Activations enter as the B operand.  To keep fp32-grade accuracy with bf16 matrix cores an
 // activation a is carried as two bf16 numbers hi = bf16(a), lo = bf16(a - hi) (16 mantissa
 // bits).  For rows <= 8 the 16 operand columns hold hi of row j in column j and lo in column
-// j+8, so one MFMA does both and the epilogue adds the two column halves; for 9..16 rows hi
+// j+8 (rows <= 4: j+4, and the loads mirror columns 4..7 into 8..11: half the bytes), so one
+// MFMA does both and the epilogue adds the two column halves; for 9..16 rows hi
 // and lo are separate operands and two MFMAs accumulate into the same registers.
 //
 // RMSNorm is folded in: the producer of x writes (gain * x) as the next operand plus per-strip
@@ -195,7 +196,7 @@ k_mat_begin(pv_dev_state *st, const int32_t *mailbox, int rows, int mode, const 
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r] = pv_bf16_to_f32(e[r]);
     }
-    emit_x<NB>(lane, rows, strip, d, v, *(const uint2 *)(gain + strip * 16 + 4 * g), x, ssq, xop, ct);
+    emit_x<NB>(lane, rows, strip, d, v, *(const uint2 *)(gain + strip * 16 + 4 * g), x, ssq, xop, ct, pv_lo_off(rows));
     if (ct != 0) return;
     for (int idx = blockIdx.x * 64 + lane; idx < rows * half; idx += gridDim.x * 64) {
         const int jj = idx / half, i = idx - jj * half;
@@ -291,7 +292,12 @@ k_gemm(const gemm_args a)
     else { const int per = (nbat + NW - 1) / NW; b = min(nbat, wave * per); bend = min(nbat, b + per); bstep = 1; }
     const size_t arr = (size_t)KT * 64;             // tiles of one strip = elements of one operand array, in uint4
     const uint4 *A = a.W + (size_t)strip0 * arr + lane;
-    const uint4 *B = a.xop + lane;                    // tile ct: hi at B + (2 ct) arr, lo at B + (2 ct + 1) arr   (NB == 2)
+    // tile ct: hi at B + (2 ct) arr, lo at B + (2 ct + 1) arr   (NB == 2).  Packed rows of a block of at most 4: hi and lo sit in
+    // columns 0..3 and 4..7 of a tile; the lanes of columns 8..11 read the lo columns again, so that the epilogue finds them
+    // where a block of 8 has them, and those of 12..15 anything in the same 128-byte line (their columns are never used): half the lines
+    int bl = lane;
+    if (NB == 1 && a.lo_off == 4) { const int col = lane & 15; bl = (lane & ~15) | (col < 8 ? col : col < 12 ? col - 4 : col - 8); }
+    const uint4 *B = a.xop + bl;
     // a ragged last workgroup re-reads its first strip for the missing ones and drops the result
     size_t so[S];
 #pragma unroll
@@ -1052,7 +1058,7 @@ static int run_block(pv_cache *c, hipStream_t s)
 
     gemm_args g = {};
     int prc;
-    g.st = c->ws.state; g.inv_d = 1.0f / (float)d; g.eps = (float)f.rms_eps; g.ssq_parts = d / 16;
+    g.st = c->ws.state; g.lo_off = pv_lo_off(rows); g.inv_d = 1.0f / (float)d; g.eps = (float)f.rms_eps; g.ssq_parts = d / 16;
     g.q_hi = (uint16_t *)c->ws.q; g.q_lo = g.q_hi + (size_t)c->rows_cap * qd; g.pool = (uint16_t *)c->d_pool; g.page_table = c->ws.page_table; g.rope = c->ws.rope; g.geom = pv_geom(c);
     g.n_q_heads = f.n_q_heads; g.q_strips = qd / 16; g.k_strips = kvd / 16;
     g.x = c->ws.x; g.d = d; g.xop_act = mw.xop_d; g.F = F;

@@ -30,15 +30,19 @@ __device__ inline uint2 load_once(const uint2 *p)
 
 // ------------------------------------------------------------------------------------------
 // Operand writers.  Element (row j, K-index k) of an activation lives at
-//   arr[(k/32)*512 + (col + 16*((k%32)/8))*8 + k%8],  col = j (hi) / j+8 (lo) when NB == 1
-//   (at most 8 rows).  When NB == 2 the rows come in column tiles of 16: tile j/16 owns a hi
+//   arr[(k/32)*512 + (col + 16*((k%32)/8))*8 + k%8],  col = j (hi) / j + lo_off (lo) when NB == 1
+//   (at most 8 rows; lo_off = 8, or 4 for blocks of at most 4 rows: columns 0..7 are then all a
+//   reader needs, half the 128-byte lines of a tile).  When NB == 2 the rows come in column tiles of 16: tile j/16 owns a hi
 //   array followed by a lo array ((K/32)*512 elements each), col = j%16 in both.
 // ------------------------------------------------------------------------------------------
 __device__ inline uint16_t bf16_rne(float f) { return pv_f32_to_bf16(f); }
 
 // four consecutive k (k0 % 4 == 0) of row j
+// lo column offset of a packed-row block of `rows` rows
+__host__ __device__ inline int pv_lo_off(int rows) { return rows <= 4 ? 4 : 8; }
+
 template <int NB>
-__device__ inline void store_operand4(uint16_t *xop, int K, int j, int k0, const float y[4])
+__device__ inline void store_operand4(uint16_t *xop, int K, int j, int k0, const float y[4], int lo_off)
 {
     uint16_t hi[4], lo[4];
 #pragma unroll
@@ -48,7 +52,7 @@ __device__ inline void store_operand4(uint16_t *xop, int K, int j, int k0, const
     const uint2 vl = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
     if (NB == 1) {
         *(uint2 *)(xop + tile + in + (size_t)j * 8) = vh;
-        *(uint2 *)(xop + tile + in + (size_t)(j + 8) * 8) = vl;
+        *(uint2 *)(xop + tile + in + (size_t)(j + lo_off) * 8) = vl;
     } else {
         const size_t arr = (size_t)(K / 32) * 512;
         uint16_t *base = xop + (size_t)(j >> 4) * 2 * arr + tile + in + (size_t)(j & 15) * 8;
